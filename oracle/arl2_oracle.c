@@ -1,0 +1,320 @@
+/*
+ * CPU oracle for the ARL^2 hybrid attention step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the plain definition of what the GPU library must compute,
+ * written out as nested loops in fp64 (plus an all-fp32 twin for the
+ * "fp32 throughout" configuration).  It shares no code, header, table or
+ * helper with the HIP path and must never be linked into or called from it.
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * What is computed, per stream b and head h (paper, Sec. 3.2 and 3.3, Alg. 1):
+ *
+ *   readout pass (state is read, never written):
+ *     s_ij    = sm_scale * <q_i, k_j>                   softmax logits, Eq. (1) scale
+ *     O_intra = softmax_j(s_ij) V                       intra-chunk branch, Eq. (2)
+ *     q'_i    = q_i / sqrt(|q_i|^2 + eps)               L2Norm part of the feature map, Eq. (3)
+ *     O_inter = q'_i S                                  same pre-update S for every token, Eq. (5), Eq. (7)
+ *     out_i   = O_intra_i + g_i * O_inter_i             headwise gate broadcast over D, Eq. (6)
+ *
+ *   commit (once per chunk, after the last denoising pass, Sec. 3.3 "clean-pass update"):
+ *     k'_i    = k_i / sqrt(|k_i|^2 + eps)               Eq. (3)
+ *     S      <- gate * S + sum_i k'_i^T v_i             Eq. (4) with beta = 1 and the
+ *                                                       delta-correction term dropped
+ *
+ * Layouts (all contiguous, row-major):
+ *   q [B][Lq][H][D], k,v [B][Lkv][H][D], g [B][Lq][H], out [B][nrows][H][D],
+ *   S [B][H][D][D] indexed S[d_k][d_v], gate [B][H].
+ * Inputs q,k,v,g are passed as float: both fp32 and bf16 stored values widen
+ * to float exactly, so the oracle sees the very numbers the GPU reads.
+ *
+ * OpenMP only distributes independent (stream, head, row) triples; it does not
+ * change any summation order.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- fp64 -- */
+
+/* One query row i of one (b,h): Eq. (2) + Eq. (3) + Eq. (5) + Eq. (6). */
+static void fwd_row_f64(int H, int Lkv, int D,
+                        const float *q_row,            /* q[b][i][h][:]              */
+                        const float *k_bh,             /* k[b][0][h][:], stride H*D  */
+                        const float *v_bh,             /* v[b][0][h][:], stride H*D  */
+                        const double *S_bh,            /* S[b][h] or NULL            */
+                        double g_i, double sm_scale, double l2_eps,
+                        double *score,                 /* scratch, Lkv               */
+                        double *out_row)               /* D                          */
+{
+    const size_t ts = (size_t)H * D;                   /* token stride of k and v    */
+
+    /* logits and their maximum */
+    double m = -INFINITY;
+    for (int j = 0; j < Lkv; ++j) {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d)
+            s += (double)q_row[d] * (double)k_bh[j * ts + d];
+        s *= sm_scale;
+        score[j] = s;
+        if (s > m) m = s;
+    }
+    /* stable softmax weights and normaliser */
+    double Z = 0.0;
+    for (int j = 0; j < Lkv; ++j) {
+        score[j] = exp(score[j] - m);
+        Z += score[j];
+    }
+    /* intra branch: each out_row[e] accumulates its terms in ascending j */
+    for (int e = 0; e < D; ++e)
+        out_row[e] = 0.0;
+    for (int j = 0; j < Lkv; ++j)
+        for (int e = 0; e < D; ++e)
+            out_row[e] += score[j] * (double)v_bh[j * ts + e];
+    for (int e = 0; e < D; ++e)
+        out_row[e] /= Z;
+    /* inter branch: normalised query times the shared state */
+    if (S_bh) {
+        double n2 = 0.0;
+        for (int d = 0; d < D; ++d)
+            n2 += (double)q_row[d] * (double)q_row[d];
+        const double nq = sqrt(n2 + l2_eps);
+        for (int e = 0; e < D; ++e) {
+            double o = 0.0;
+            for (int d = 0; d < D; ++d)
+                o += ((double)q_row[d] / nq) * S_bh[(size_t)d * D + e];
+            out_row[e] += g_i * o;
+        }
+    }
+}
+
+/*
+ * Readout pass for a list of query rows.  rows == NULL means all Lq rows
+ * (nrows must then equal Lq).  out is [B][nrows][H][D].
+ * S == NULL: zero state (pure softmax).  g == NULL: gate of one.
+ * Returns 0, or -1 on allocation failure.
+ */
+int arl2o_fwd_f64(int B, int H, int Lq, int Lkv, int D,
+                  const float *q, const float *k, const float *v,
+                  const double *S, const float *g,
+                  double sm_scale, double l2_eps,
+                  const int32_t *rows, int nrows,
+                  double *out)
+{
+    int fail = 0;
+    const long total = (long)B * H * nrows;
+#pragma omp parallel
+    {
+        double *score = (double *)malloc(sizeof(double) * (size_t)(Lkv > 0 ? Lkv : 1));
+        if (!score) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 4)
+            for (long t = 0; t < total; ++t) {
+                const int r = (int)(t % nrows);
+                const int h = (int)((t / nrows) % H);
+                const int b = (int)(t / ((long)nrows * H));
+                const int i = rows ? rows[r] : r;
+                const float *q_row = q + (((size_t)b * Lq + i) * H + h) * D;
+                const float *k_bh = k + ((size_t)b * Lkv * H + h) * D;
+                const float *v_bh = v + ((size_t)b * Lkv * H + h) * D;
+                const double *S_bh = S ? S + ((size_t)b * H + h) * D * D : NULL;
+                const double g_i = g ? (double)g[((size_t)b * Lq + i) * H + h] : 1.0;
+                double *out_row = out + (((size_t)b * nrows + r) * H + h) * D;
+                fwd_row_f64(H, Lkv, D, q_row, k_bh, v_bh, S_bh, g_i, sm_scale, l2_eps,
+                            score, out_row);
+            }
+        }
+        free(score);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Commit: S[b][h] <- gate[b][h] * S[b][h] + sum_i k'_i^T v_i, in place.
+ * The gate multiplies the old state only; the new outer products enter un-gated.
+ */
+int arl2o_commit_f64(int B, int H, int L, int D,
+                     const float *k, const float *v, const double *gate,
+                     double l2_eps, double *S)
+{
+    const size_t ts = (size_t)H * D;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S_bh = S + ((size_t)b * H + h) * D * D;
+            const float *k_bh = k + ((size_t)b * L * H + h) * D;
+            const float *v_bh = v + ((size_t)b * L * H + h) * D;
+            /* acc[d][e] = sum_i k'_i[d] * v_i[e]; every element adds its terms in ascending i */
+            double *acc = (double *)calloc((size_t)D * D + (size_t)D, sizeof(double));
+            if (!acc) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            double *kp = acc + (size_t)D * D;          /* one normalised key row, Eq. (3) */
+            for (int i = 0; i < L; ++i) {
+                double n2 = 0.0;
+                for (int d = 0; d < D; ++d)
+                    n2 += (double)k_bh[i * ts + d] * (double)k_bh[i * ts + d];
+                const double nk = sqrt(n2 + l2_eps);
+                for (int d = 0; d < D; ++d)
+                    kp[d] = (double)k_bh[i * ts + d] / nk;
+                for (int d = 0; d < D; ++d)
+                    for (int e = 0; e < D; ++e)
+                        acc[(size_t)d * D + e] += kp[d] * (double)v_bh[i * ts + e];
+            }
+            const double a = gate[(size_t)b * H + h];
+            for (int d = 0; d < D; ++d)
+                for (int e = 0; e < D; ++e)
+                    S_bh[(size_t)d * D + e] = a * S_bh[(size_t)d * D + e] + acc[(size_t)d * D + e];
+            free(acc);
+        }
+    }
+    return fail ? -1 : 0;
+}
+
+/* ---------------------------------------------------------------- fp32 -- */
+/* The same two definitions with every operation in float: the reference for
+ * the configuration that is specified as fp32 throughout.                    */
+
+static void fwd_row_f32(int H, int Lkv, int D,
+                        const float *q_row, const float *k_bh, const float *v_bh,
+                        const float *S_bh, float g_i, float sm_scale, float l2_eps,
+                        float *score, float *out_row)
+{
+    const size_t ts = (size_t)H * D;
+    float m = -INFINITY;
+    for (int j = 0; j < Lkv; ++j) {
+        float s = 0.0f;
+        for (int d = 0; d < D; ++d)
+            s += q_row[d] * k_bh[j * ts + d];
+        s *= sm_scale;
+        score[j] = s;
+        if (s > m) m = s;
+    }
+    float Z = 0.0f;
+    for (int j = 0; j < Lkv; ++j) {
+        score[j] = expf(score[j] - m);
+        Z += score[j];
+    }
+    for (int e = 0; e < D; ++e)
+        out_row[e] = 0.0f;
+    for (int j = 0; j < Lkv; ++j)
+        for (int e = 0; e < D; ++e)
+            out_row[e] += score[j] * v_bh[j * ts + e];
+    for (int e = 0; e < D; ++e)
+        out_row[e] /= Z;
+    if (S_bh) {
+        float n2 = 0.0f;
+        for (int d = 0; d < D; ++d)
+            n2 += q_row[d] * q_row[d];
+        const float nq = sqrtf(n2 + l2_eps);
+        for (int e = 0; e < D; ++e) {
+            float o = 0.0f;
+            for (int d = 0; d < D; ++d)
+                o += (q_row[d] / nq) * S_bh[(size_t)d * D + e];
+            out_row[e] += g_i * o;
+        }
+    }
+}
+
+int arl2o_fwd_f32(int B, int H, int Lq, int Lkv, int D,
+                  const float *q, const float *k, const float *v,
+                  const float *S, const float *g,
+                  float sm_scale, float l2_eps,
+                  const int32_t *rows, int nrows,
+                  float *out)
+{
+    int fail = 0;
+    const long total = (long)B * H * nrows;
+#pragma omp parallel
+    {
+        float *score = (float *)malloc(sizeof(float) * (size_t)(Lkv > 0 ? Lkv : 1));
+        if (!score) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 4)
+            for (long t = 0; t < total; ++t) {
+                const int r = (int)(t % nrows);
+                const int h = (int)((t / nrows) % H);
+                const int b = (int)(t / ((long)nrows * H));
+                const int i = rows ? rows[r] : r;
+                const float *q_row = q + (((size_t)b * Lq + i) * H + h) * D;
+                const float *k_bh = k + ((size_t)b * Lkv * H + h) * D;
+                const float *v_bh = v + ((size_t)b * Lkv * H + h) * D;
+                const float *S_bh = S ? S + ((size_t)b * H + h) * D * D : NULL;
+                const float g_i = g ? g[((size_t)b * Lq + i) * H + h] : 1.0f;
+                float *out_row = out + (((size_t)b * nrows + r) * H + h) * D;
+                fwd_row_f32(H, Lkv, D, q_row, k_bh, v_bh, S_bh, g_i, sm_scale, l2_eps,
+                            score, out_row);
+            }
+        }
+        free(score);
+    }
+    return fail ? -1 : 0;
+}
+
+int arl2o_commit_f32(int B, int H, int L, int D,
+                     const float *k, const float *v, const float *gate,
+                     float l2_eps, float *S)
+{
+    const size_t ts = (size_t)H * D;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            float *S_bh = S + ((size_t)b * H + h) * D * D;
+            const float *k_bh = k + ((size_t)b * L * H + h) * D;
+            const float *v_bh = v + ((size_t)b * L * H + h) * D;
+            /* acc[d][e] = sum_i k'_i[d] * v_i[e]; every element adds its terms in ascending i */
+            float *acc = (float *)calloc((size_t)D * D + (size_t)D, sizeof(float));
+            if (!acc) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            float *kp = acc + (size_t)D * D;          /* one normalised key row, Eq. (3) */
+            for (int i = 0; i < L; ++i) {
+                float n2 = 0.0;
+                for (int d = 0; d < D; ++d)
+                    n2 += (float)k_bh[i * ts + d] * (float)k_bh[i * ts + d];
+                const float nk = sqrtf(n2 + l2_eps);
+                for (int d = 0; d < D; ++d)
+                    kp[d] = (float)k_bh[i * ts + d] / nk;
+                for (int d = 0; d < D; ++d)
+                    for (int e = 0; e < D; ++e)
+                        acc[(size_t)d * D + e] += kp[d] * (float)v_bh[i * ts + e];
+            }
+            const float a = gate[(size_t)b * H + h];
+            for (int d = 0; d < D; ++d)
+                for (int e = 0; e < D; ++e)
+                    S_bh[(size_t)d * D + e] = a * S_bh[(size_t)d * D + e] + acc[(size_t)d * D + e];
+            free(acc);
+        }
+    }
+    return fail ? -1 : 0;
+}
+
+int arl2o_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,156 @@
+"""ctypes front end of the CPU oracle (``arl2_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Nothing here touches the GPU library, and the GPU library never imports this
+module: the oracle is the independent definition that parity tests compare
+against.  Only ``tests/``, the smoke check and the benchmark's ``cpu_baseline``
+leg may use it.
+
+Array conventions (numpy, C-contiguous):
+  q [B,Lq,H,D], k,v [B,Lkv,H,D], g [B,Lq,H], S [B,H,D,D] (S[d_k, d_v]), gate [B,H].
+q,k,v,g are converted to float32, which is exact for fp32 and bf16 stored
+values; S and gate are float64 in the fp64 oracle.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "arl2_oracle.c")
+_LIB = os.path.join(_HERE, "libarl2_oracle.so")
+_lib = None
+
+L2_EPS = 1e-6  # the paper gives no epsilon for L2Norm in Eq. (3); this is the chosen reading
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc.  Building the checker is not using it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-march=native", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32, f64, f32, vp = ctypes.c_int, ctypes.c_double, ctypes.c_float, ctypes.c_void_p
+        lib.arl2o_fwd_f64.argtypes = [i32] * 5 + [vp] * 5 + [f64, f64, vp, i32, vp]
+        lib.arl2o_fwd_f64.restype = i32
+        lib.arl2o_commit_f64.argtypes = [i32] * 4 + [vp] * 3 + [f64, vp]
+        lib.arl2o_commit_f64.restype = i32
+        lib.arl2o_fwd_f32.argtypes = [i32] * 5 + [vp] * 5 + [f32, f32, vp, i32, vp]
+        lib.arl2o_fwd_f32.restype = i32
+        lib.arl2o_commit_f32.argtypes = [i32] * 4 + [vp] * 3 + [f32, vp]
+        lib.arl2o_commit_f32.restype = i32
+        lib.arl2o_num_threads.restype = i32
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loops actually use."""
+    return int(_load().arl2o_num_threads())
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(np.asarray(a), dtype=dtype)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_shapes(q, k, v, S, g):
+    if q.ndim != 4 or k.ndim != 4 or v.ndim != 4:
+        raise ValueError("q, k, v must be [B, L, H, D]")
+    B, Lq, H, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[2] != H or k.shape[3] != D:
+        raise ValueError("k, v must be [B, Lkv, H, D] matching q")
+    if S is not None and S.shape != (B, H, D, D):
+        raise ValueError("S must be [B, H, D, D]")
+    if g is not None and g.shape != (B, Lq, H):
+        raise ValueError("g must be [B, Lq, H]")
+    return B, H, Lq, k.shape[1], D
+
+
+def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: float = L2_EPS,
+        rows: Optional[Sequence[int]] = None, precision: str = "f64") -> np.ndarray:
+    """Readout pass: out = softmax(q k^T * sm_scale) v + g * L2Norm(q) S   (Eq. 2, 3, 5, 6).
+
+    ``rows`` restricts the computation to those query indices (each output row
+    depends only on its own q row and on all of k, v, S); the result is then
+    [B, len(rows), H, D].  ``precision`` is "f64" or "f32" (every operation in float).
+    """
+    lib = _load()
+    q, k, v = _c(q, np.float32), _c(k, np.float32), _c(v, np.float32)
+    g = None if g is None else _c(g, np.float32)
+    st = np.float64 if precision == "f64" else np.float32
+    S = None if S is None else _c(S, st)
+    B, H, Lq, Lkv, D = _check_shapes(q, k, v, S, g)
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(D)  # Eq. (1)
+    if rows is None:
+        rows_arr, nrows = None, Lq
+    else:
+        rows_arr = _c(rows, np.int32)
+        nrows = int(rows_arr.size)
+        if nrows and (rows_arr.min() < 0 or rows_arr.max() >= Lq):
+            raise ValueError("row index out of range")
+    out = np.empty((B, nrows, H, D), dtype=st)
+    fn = lib.arl2o_fwd_f64 if precision == "f64" else lib.arl2o_fwd_f32
+    rc = fn(B, H, Lq, Lkv, D, _ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(g),
+            float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
+    if rc != 0:
+        raise MemoryError("oracle fwd failed")
+    return out
+
+
+def commit(k, v, gate, S, *, l2_eps: float = L2_EPS, precision: str = "f64") -> np.ndarray:
+    """State commit: returns gate * S + sum_i L2Norm(k_i)^T v_i   (Eq. 3, Eq. 4 with beta = 1,
+    no delta term).  The input S is left untouched; a new array is returned."""
+    lib = _load()
+    k, v = _c(k, np.float32), _c(v, np.float32)
+    st = np.float64 if precision == "f64" else np.float32
+    if k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("k, v must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    gate = _c(gate, st)
+    S_new = np.array(S, dtype=st, order="C", copy=True)
+    if gate.shape != (B, H) or S_new.shape != (B, H, D, D):
+        raise ValueError("gate must be [B, H] and S [B, H, D, D]")
+    fn = lib.arl2o_commit_f64 if precision == "f64" else lib.arl2o_commit_f32
+    rc = fn(B, H, L, D, _ptr(k), _ptr(v), _ptr(gate), float(l2_eps), _ptr(S_new))
+    if rc != 0:
+        raise MemoryError("oracle commit failed")
+    return S_new
+
+
+def rollout(chunks, S0=None, *, l2_eps: float = L2_EPS, precision: str = "f64", rows=None):
+    """Alg. 1's call pattern on given tensors: S starts at zero (or S0); per chunk every
+    readout pass sees the same pre-update S, then one commit on the clean k, v.
+
+    ``chunks`` is an iterable of dicts with keys
+      "passes": list of (q, k, v, g) tuples,  "k_clean", "v_clean", "gate".
+    Returns (list of per-chunk lists of outputs, list of S after each commit).
+    """
+    st = np.float64 if precision == "f64" else np.float32
+    S = None if S0 is None else np.array(S0, dtype=st, copy=True)
+    outs, states = [], []
+    for ch in chunks:
+        if S is None:
+            B, _, H, D = np.asarray(ch["k_clean"]).shape
+            S = np.zeros((B, H, D, D), dtype=st)
+        chunk_outs = [fwd(q, k, v, S, g, l2_eps=l2_eps, rows=rows, precision=precision)
+                      for (q, k, v, g) in ch["passes"]]
+        outs.append(chunk_outs)
+        S = commit(ch["k_clean"], ch["v_clean"], ch["gate"], S, l2_eps=l2_eps, precision=precision)
+        states.append(S.copy())
+    return outs, states

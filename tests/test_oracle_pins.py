@@ -1,0 +1,287 @@
+"""Pins for the CPU oracle: hand-derived values, closed forms, library routines,
+brute-force unrollings and invariants.  None of these re-uses the oracle's code.
+
+Each pin names the mistake it is there to catch.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+rng = np.random.default_rng(1234)
+
+
+def rand(*shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float32)
+
+
+def l2n(x, eps):
+    x = x.astype(np.float64)
+    return x / np.sqrt((x * x).sum(-1, keepdims=True) + eps)
+
+
+# ---------------------------------------------------------------- hand-derived values
+
+def test_hand_example_fwd(oracle):
+    ex = json.load(open(os.path.join(HERE, "golden", "hand_example.json")))["fwd"]
+    k = np.array([[0.0, 0.0], [math.log(3.0) / 3.0, 0.0]], dtype=np.float64)
+    q = np.array(ex["q"])[None, :, None, :]
+    v = np.array(ex["v"])[None, :, None, :]
+    S = np.array(ex["S"])[None, None]
+    g = np.array(ex["g"])[None, :, None]
+    # float32 storage of ln3/3 is inexact; recompute the expected weights from the stored value
+    k32 = k.astype(np.float32)
+    w2 = math.exp(3.0 * float(k32[1, 0]))
+    p = np.array([1.0, w2]) / (1.0 + w2)
+    assert abs(p[1] - 0.75) < 1e-7
+    out = oracle.fwd(q, k32[None, :, None, :], v, S, g, sm_scale=ex["sm_scale"], l2_eps=ex["l2_eps"])
+    np.testing.assert_allclose(out[0, :, 0, :], np.array(ex["out"]), rtol=0, atol=2e-6)
+    o_intra = oracle.fwd(q, k32[None, :, None, :], v, None, None, sm_scale=1.0, l2_eps=0.0)
+    np.testing.assert_allclose(o_intra[0, :, 0, :], np.array(ex["O_intra"]), rtol=0, atol=2e-6)
+    # inter branch alone: out(g=1) - out(S=None)
+    o_full = oracle.fwd(q, k32[None, :, None, :], v, S, None, sm_scale=1.0, l2_eps=0.0)
+    np.testing.assert_allclose((o_full - o_intra)[0, :, 0, :], np.array(ex["O_inter"]), rtol=0, atol=1e-12)
+
+
+def test_hand_example_commit(oracle):
+    ex = json.load(open(os.path.join(HERE, "golden", "hand_example.json")))["commit"]
+    k = np.array(ex["k"])[None, :, None, :]
+    v = np.array(ex["v"])[None, :, None, :]
+    S_old = np.array(ex["S_old"])[None, None]
+    for prec, tol in (("f64", 1e-12), ("f32", 1e-5)):
+        S_new = oracle.commit(k, v, np.array([[ex["gate"]]]), S_old, l2_eps=ex["l2_eps"], precision=prec)
+        np.testing.assert_allclose(S_new[0, 0], np.array(ex["S_new"]), rtol=0, atol=tol)
+    # the input state is not modified by the wrapper
+    assert np.array_equal(S_old[0, 0], np.array(ex["S_old"]))
+
+
+# ---------------------------------------------------------------- library routine: zero state = softmax attention
+
+@pytest.mark.parametrize("B,H,Lq,Lkv,D", [(1, 2, 64, 64, 64), (2, 3, 37, 53, 128), (1, 1, 5, 1, 8)])
+def test_zero_state_is_softmax_attention(oracle, B, H, Lq, Lkv, D):
+    """Catches: wrong scale, softmax over the wrong axis, q/k/v indexing or stride mistakes."""
+    q, k, v = rand(B, Lq, H, D), rand(B, Lkv, H, D), rand(B, Lkv, H, D)
+    tq, tk, tv = (torch.from_numpy(x).double().permute(0, 2, 1, 3) for x in (q, k, v))
+    ref = torch.softmax(tq @ tk.transpose(-1, -2) / math.sqrt(D), dim=-1) @ tv
+    ref = ref.permute(0, 2, 1, 3).numpy()
+    for S in (None, np.zeros((B, H, D, D))):
+        out = oracle.fwd(q, k, v, S, None)
+        np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    out32 = oracle.fwd(q, k, v, None, None, precision="f32")
+    np.testing.assert_allclose(out32, ref, rtol=0, atol=2e-6)
+    # torch's fused kernel as a second library routine
+    ref2 = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(oracle.fwd(q, k, v), ref2, rtol=1e-10, atol=1e-12)
+
+
+def test_softmax_closed_forms(oracle):
+    """v == 1 gives 1; k == 0 gives the column mean of v; large logits stay finite."""
+    B, H, L, D = 1, 2, 19, 16
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    np.testing.assert_allclose(oracle.fwd(q, k, np.ones_like(v)), 1.0, rtol=1e-14)
+    out = oracle.fwd(q, np.zeros_like(k), v)
+    np.testing.assert_allclose(out, np.broadcast_to(v.astype(np.float64).mean(1, keepdims=True), out.shape), rtol=1e-13, atol=1e-15)
+    big = oracle.fwd(q * 300, k * 300, v)
+    assert np.isfinite(big).all()
+    # with huge logits softmax picks the arg-max key's value
+    s = np.einsum("blhd,bmhd->bhlm", q.astype(np.float64) * 300, k.astype(np.float64) * 300)
+    pick = s.argmax(-1)  # [B,H,L]
+    want = np.stack([[v[b, pick[b, h], h, :] for h in range(H)] for b in range(B)])  # [B,H,L,D]
+    np.testing.assert_allclose(big, want.transpose(0, 2, 1, 3), rtol=0, atol=1e-6)
+
+
+# ---------------------------------------------------------------- inter branch
+
+def test_inter_branch_matches_einsum(oracle):
+    """out(S) - out(0) = g * L2Norm(q) S, with d_k contracted (not d_v)."""
+    B, H, L, D = 2, 3, 11, 32
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    g = rng.uniform(0, 1, (B, L, H)).astype(np.float32)
+    eps = 1e-6
+    diff = oracle.fwd(q, k, v, S, g) - oracle.fwd(q, k, v, None, None)
+    want = np.einsum("blhd,bhde->blhe", l2n(q, eps), S) * g[..., None].astype(np.float64)
+    np.testing.assert_allclose(diff, want, rtol=1e-10, atol=1e-12)
+    # g == None means a gate of one; g == 0 switches the branch off
+    diff1 = oracle.fwd(q, k, v, S, None) - oracle.fwd(q, k, v, None, None)
+    np.testing.assert_allclose(diff1, np.einsum("blhd,bhde->blhe", l2n(q, eps), S), rtol=1e-10, atol=1e-12)
+    assert np.array_equal(oracle.fwd(q, k, v, S, np.zeros_like(g)), oracle.fwd(q, k, v, None, None))
+
+
+def test_query_scale_invariance_and_linearity(oracle):
+    """L2Norm makes O_inter independent of |q| (O_intra is not); out is affine in S."""
+    B, H, L, D = 1, 2, 9, 16
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    S1, S2 = rng.standard_normal((B, H, D, D)), rng.standard_normal((B, H, D, D))
+    o0 = oracle.fwd(q, k, v, None, None, l2_eps=0.0)
+    i1 = oracle.fwd(q, k, v, S1, None, l2_eps=0.0) - o0
+    i1_scaled = oracle.fwd(4 * q, k, v, S1, None, l2_eps=0.0) - oracle.fwd(4 * q, k, v, None, None, l2_eps=0.0)
+    np.testing.assert_allclose(i1, i1_scaled, rtol=1e-9, atol=1e-12)
+    assert np.abs(oracle.fwd(4 * q, k, v) - o0).max() > 1e-3
+    i2 = oracle.fwd(q, k, v, S2, None, l2_eps=0.0) - o0
+    i12 = oracle.fwd(q, k, v, S1 + S2, None, l2_eps=0.0) - o0
+    np.testing.assert_allclose(i12, i1 + i2, rtol=1e-9, atol=1e-11)
+
+
+def test_zero_rows_do_not_produce_nan(oracle):
+    """An all-zero q or k row is defined by eps: it contributes 0, not NaN."""
+    B, H, L, D = 1, 1, 4, 8
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    q[0, 1] = 0
+    k[0, 2] = 0
+    S = rng.standard_normal((B, H, D, D))
+    out = oracle.fwd(q, k, v, S, None)
+    assert np.isfinite(out).all()
+    np.testing.assert_allclose(out[0, 1], oracle.fwd(q, k, v)[0, 1], rtol=1e-14)
+    Sn = oracle.commit(k, v, np.ones((B, H)), np.zeros((B, H, D, D)))
+    assert np.isfinite(Sn).all()
+    k2, v2 = np.delete(k, 2, axis=1), np.delete(v, 2, axis=1)
+    np.testing.assert_allclose(Sn, oracle.commit(k2, v2, np.ones((B, H)), np.zeros((B, H, D, D))), rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------- commit
+
+def test_commit_matches_einsum_and_gate_cases(oracle):
+    """Catches: transposed outer product, gate applied to the new term, k not normalised."""
+    B, H, L, D = 2, 3, 23, 16
+    k, v = rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    gate = rng.uniform(0.5, 1.0, (B, H))
+    eps = 1e-6
+    kv = np.einsum("blhd,blhe->bhde", l2n(k, eps), v.astype(np.float64))
+    np.testing.assert_allclose(oracle.commit(k, v, gate, S), gate[..., None, None] * S + kv, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(oracle.commit(k, v, np.zeros((B, H)), S), kv, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(oracle.commit(k, v, np.ones((B, H)), S), S + kv, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(oracle.commit(k, v, gate, S, precision="f32"), gate[..., None, None] * S + kv, rtol=0, atol=2e-5)
+
+
+def test_associative_memory_identity(oracle):
+    """One stored (k, v) pair, gate 1, S = 0: querying with c*k returns v exactly (|k'| = 1)."""
+    D = 16
+    k, v = rand(1, 1, 1, D), rand(1, 1, 1, D)
+    S = oracle.commit(k, v, np.ones((1, 1)), np.zeros((1, 1, D, D)), l2_eps=0.0)
+    for c in (1.0, 0.25, 7.0):
+        q = (c * k).astype(np.float32)
+        inter = oracle.fwd(q, k, v, S, None, l2_eps=0.0) - oracle.fwd(q, k, v, None, None, l2_eps=0.0)
+        np.testing.assert_allclose(inter[0, 0, 0], v[0, 0, 0].astype(np.float64), rtol=1e-6, atol=1e-7)
+
+
+def _tiny_rollout_inputs(N=4, P=2, B=1, H=2, L=12, D=8):
+    chunks = []
+    for _ in range(N):
+        passes = [(rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D),
+                   rng.uniform(0.45, 0.55, (B, L, H)).astype(np.float32)) for _ in range(P)]
+        chunks.append({"passes": passes, "k_clean": rand(B, L, H, D), "v_clean": rand(B, L, H, D),
+                       "gate": rng.uniform(0.85, 0.99, (B, H))})
+    return chunks
+
+
+def test_state_is_unrolled_gated_sum(oracle):
+    """After N commits S_N = sum_j (prod_{i>j} gate_i) K'_j^T V_j, computed with no running state."""
+    chunks = _tiny_rollout_inputs()
+    _, states = oracle.rollout(chunks)
+    eps = oracle.L2_EPS
+    for N in range(1, len(chunks) + 1):
+        want = 0.0
+        for j in range(N):
+            decay = np.ones_like(chunks[0]["gate"])
+            for i in range(j + 1, N):
+                decay = decay * chunks[i]["gate"]
+            kv = np.einsum("blhd,blhe->bhde", l2n(chunks[j]["k_clean"], eps), chunks[j]["v_clean"].astype(np.float64))
+            want = want + decay[..., None, None] * kv
+        np.testing.assert_allclose(states[N - 1], want, rtol=1e-11, atol=1e-12)
+
+
+def test_inter_readout_is_cross_chunk_linear_attention(oracle):
+    """O_inter of chunk N equals sum_{j<N} decay * (Q' K'_j^T) V_j: a score-matrix form that never builds S."""
+    chunks = _tiny_rollout_inputs()
+    outs, _ = oracle.rollout(chunks)
+    eps = oracle.L2_EPS
+    for N, ch in enumerate(chunks):
+        for p, (q, k, v, g) in enumerate(ch["passes"]):
+            intra = oracle.fwd(q, k, v, None, None)
+            want = np.zeros_like(intra)
+            for j in range(N):
+                decay = np.ones_like(chunks[0]["gate"])
+                for i in range(j + 1, N):
+                    decay = decay * chunks[i]["gate"]
+                scores = np.einsum("blhd,bmhd->bhlm", l2n(q, eps), l2n(chunks[j]["k_clean"], eps))
+                want += np.einsum("bhlm,bmhe->blhe", scores * decay[..., None, None], chunks[j]["v_clean"].astype(np.float64))
+            want = intra + g[..., None].astype(np.float64) * want
+            np.testing.assert_allclose(outs[N][p], want, rtol=1e-10, atol=1e-11)
+
+
+def test_all_tokens_see_the_same_state(oracle):
+    """Readout is permutation-equivariant over the chunk's tokens and commit is permutation-invariant:
+    a token-sequential state update would fail both."""
+    B, H, L, D = 1, 2, 17, 8
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    g = rng.uniform(0, 1, (B, L, H)).astype(np.float32)
+    S = rng.standard_normal((B, H, D, D))
+    perm = rng.permutation(L)
+    out = oracle.fwd(q, k, v, S, g)
+    out_p = oracle.fwd(q[:, perm], k[:, perm], v[:, perm], S, g[:, perm])
+    np.testing.assert_allclose(out_p, out[:, perm], rtol=1e-11, atol=1e-12)
+    # reordering only the keys/values leaves every row unchanged
+    np.testing.assert_allclose(oracle.fwd(q, k[:, perm], v[:, perm], S, g), out, rtol=1e-11, atol=1e-12)
+    gate = np.full((B, H), 0.9)
+    np.testing.assert_allclose(oracle.commit(k[:, perm], v[:, perm], gate, S), oracle.commit(k, v, gate, S), rtol=1e-11, atol=1e-12)
+    # row subset: each row depends only on its own q and g
+    rows = [3, 0, 16]
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, S, g, rows=rows), out[:, rows])
+
+
+def test_state_is_read_only_in_readout(oracle):
+    """Denoising passes never write S; only commit changes it."""
+    B, H, L, D = 1, 2, 10, 8
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    S = np.ascontiguousarray(rng.standard_normal((B, H, D, D)))
+    snap = S.tobytes()
+    first = oracle.fwd(q, k, v, S, None)
+    for _ in range(3):
+        assert np.array_equal(oracle.fwd(q, k, v, S, None), first)
+    assert S.tobytes() == snap
+    S2 = oracle.commit(k, v, np.full((B, H), 0.9), S)
+    assert S.tobytes() == snap and not np.array_equal(S2, S)
+    # rollout: every pass of a chunk used the pre-update state of that chunk
+    chunks = _tiny_rollout_inputs(N=3, P=3)
+    outs, states = oracle.rollout(chunks)
+    Sprev = np.zeros_like(states[0])
+    for n, ch in enumerate(chunks):
+        for p, (q, k, v, g) in enumerate(ch["passes"]):
+            assert np.array_equal(outs[n][p], oracle.fwd(q, k, v, Sprev, g))
+        Sprev = states[n]
+
+
+def test_f32_and_f64_oracles_agree_on_tiny_workload(oracle):
+    """Bounds the fp32 oracle's own rounding on the fp32-throughout configuration."""
+    import workloads as W
+    w = W.WORKLOADS["tiny"]
+    S64 = np.zeros((w.B, w.H, w.D, w.D))
+    S32 = S64.astype(np.float32)
+    for c in range(w.chunks):
+        for p in range(w.passes):
+            q, k, v, g = (W.as_f32_numpy(t) for t in W.pass_inputs(w, c, p))
+            o64, o32 = oracle.fwd(q, k, v, S64, g), oracle.fwd(q, k, v, S32, g, precision="f32")
+            assert np.abs(o64 - o32).max() <= 1e-5 * max(np.abs(o64).max(), 1e-30)
+        k, v, gate = (W.as_f32_numpy(t) for t in W.clean_inputs(w, c))
+        S64 = oracle.commit(k, v, gate, S64)
+        S32 = oracle.commit(k, v, gate, S32, precision="f32")
+        assert np.abs(S64 - S32).max() <= 1e-5 * np.abs(S64).max()
+
+
+def test_stored_bf16_values_reach_the_oracle_exactly():
+    import workloads as W
+    w = W.WORKLOADS["ragged_small"]
+    q, _, _, _ = W.pass_inputs(w, 0, 0)
+    assert q.dtype == torch.bfloat16
+    f = W.as_f32_numpy(q)
+    assert torch.equal(torch.from_numpy(f).to(torch.bfloat16), q)
+    q2, _, _, _ = W.pass_inputs(w, 0, 0)
+    assert torch.equal(q, q2)
+    q3, _, _, _ = W.pass_inputs(w, 0, 1)
+    assert not torch.equal(q, q3)
