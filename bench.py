@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the ARL^2 hybrid attention chunk step on one MI355X.
+
+One "step" is one pass of the whole hot path over one chunk of synthetic input: `passes`
+read-only denoising passes (arl2_hybrid_attn_fwd) that all see the same state, then one
+arl2_state_commit.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-step throughput in chunk tokens/s, the roofline figures of the dominant
+kernel (the fused flash + readout kernel, timed live with HIP events on the launch stream), and the
+CPU oracle timed on a bounded sample of the same workload as a baseline for context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def fwd_flops(B, H, L, D):
+    """Algorithmic flops of one readout pass: QK^T and PV (4 L^2 D) plus the state readout (2 L D^2)."""
+    return B * H * (4.0 * L * L * D + 2.0 * L * D * D)
+
+
+def commit_flops(B, H, L, D):
+    return B * H * 2.0 * L * D * D
+
+
+def fwd_bytes(B, H, L, D, io_bytes):
+    return B * (4.0 * L * H * D * io_bytes + H * D * D * 4.0 + L * H * 4.0)
+
+
+def commit_bytes(B, H, L, D, io_bytes):
+    return B * (2.0 * L * H * D * io_bytes + 2.0 * H * D * D * 4.0)
+
+
+def cpu_baseline(w, passes_inputs, clean, S0, rows_per_head):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample: `rows_per_head`
+    query rows of one readout pass (every row costs the same) and one full commit; the chunk step
+    time is extrapolated as passes * (row time * L / rows) + commit time."""
+    import numpy as np
+
+    import workloads as W
+    from oracle import arl2_oracle as O
+    O.build()
+    f = W.as_f32_numpy
+    q, k, v, g = passes_inputs[0]
+    rows = np.linspace(0, w.L - 1, rows_per_head).astype(np.int32)
+    S64 = S0.astype(np.float64)
+    qf, kf, vf, gf = f(q), f(k), f(v), f(g)
+    t0 = time.perf_counter()
+    O.fwd(qf, kf, vf, S64, gf, rows=rows)
+    t_rows = time.perf_counter() - t0
+    kc, vc, gate = clean
+    kcf, vcf, gatef = f(kc), f(vc), f(gate)
+    t0 = time.perf_counter()
+    O.commit(kcf, vcf, gatef, S64)
+    t_commit = time.perf_counter() - t0
+    t_step = w.passes * t_rows * (w.L / len(rows)) + t_commit
+    return {
+        "value": w.B * w.L / t_step, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+        "sample": f"fp64 oracle: {len(rows)} of {w.L} query rows per head of one readout pass "
+                  f"({t_rows:.2f} s) + one full commit ({t_commit:.2f} s); step time extrapolated to "
+                  f"{w.passes} passes + 1 commit = {t_step:.1f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="query rows per head timed on the CPU oracle")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (heads and streams are independent, so the step "
+              "shards without any exchange); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2605_16579_amd as A
+    import workloads as W
+
+    A.load_library()   # fails loudly if the HIP library is missing: there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = W.WORKLOADS[args.workload]
+    io_bytes = 2 if w.io_dtype == "bf16" else 4
+
+    # ---- inputs, resident in HBM
+    passes_cpu = [W.pass_inputs(w, 0, p) for p in range(w.passes)]
+    clean_cpu = W.clean_inputs(w, 0)
+    passes = [tuple(t.to(dev) for t in pi) for pi in passes_cpu]
+    kc, vc, gate = (t.to(dev) for t in clean_cpu)
+    outs = [torch.empty_like(passes[p][0]) for p in range(w.passes)]
+    S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
+    ws = A.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype, device=dev)
+    for j in range(w.prefill):     # input preparation: the state the chunk starts from
+        pk, pv, pg = (t.to(dev) for t in W.prefill_inputs(w, j))
+        A.arl2_state_commit(pk, pv, pg, S, ws)
+    torch.cuda.synchronize()
+    S0 = S.detach().cpu().numpy().copy()
+
+    def step(events=None):
+        for p in range(w.passes):
+            q, k, v, g = passes[p]
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+        if events is not None:
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record()
+        A.arl2_state_commit(kc, vc, gate, S, ws)
+        if events is not None:
+            c1.record()
+            events.append((c0, c1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * t_total / args.steps
+    per_step = w.passes + 1
+    fwd_ms = [e0.elapsed_time(e1) for i, (e0, e1) in enumerate(events) if i % per_step != w.passes]
+    com_ms = [e0.elapsed_time(e1) for i, (e0, e1) in enumerate(events) if i % per_step == w.passes]
+    fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
+    com_avg_ms = sum(com_ms) / len(com_ms)
+
+    ff, cf = fwd_flops(w.B, w.H, w.L, w.D), commit_flops(w.B, w.H, w.L, w.D)
+    step_flops = w.passes * ff + cf
+    fwd_tflops = ff / (fwd_avg_ms * 1e-3) / 1e12
+    step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+    result = {
+        "metric": "hybrid-attn tokens/s + TFLOP/s (% bf16 MFMA peak) per chunk step, 4680 tok",
+        "value": w.B * w.L / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.io_dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
+                   "passes": w.passes, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
+        "step_tflops": step_tflops,
+        "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,
+        "token_passes_per_s": w.B * w.L * w.passes / (ms_per_step * 1e-3),
+        "fwd_ms": fwd_avg_ms, "fwd_ms_min": min(fwd_ms),
+        "commit_ms": com_avg_ms, "commit_ms_min": min(com_ms),
+        "commit_gbs": commit_bytes(w.B, w.H, w.L, w.D, io_bytes) / (com_avg_ms * 1e-3) / 1e9,
+        "commit_frac_hbm_peak": commit_bytes(w.B, w.H, w.L, w.D, io_bytes) / (com_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "fwd_gbs": fwd_bytes(w.B, w.H, w.L, w.D, io_bytes) / (fwd_avg_ms * 1e-3) / 1e9,
+        "roofline": {"kernel": "fwd_bf16_kernel (flash softmax + fused state readout)",
+                     "bound": "mfma", "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": fwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        t = json.load(open(traffic_file)).get(w.name)
+        if t:
+            result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_rows)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,113 @@
+/*
+ * arl2.h -- C ABI of the MI355X (gfx950) library for the ARL^2 hybrid attention step
+ * of "Attend Locally, Remember Linearly" (paper Sec. 3.2, Sec. 3.3, Alg. 1).
+ *
+ * Two operations make up the step:
+ *
+ *   arl2_hybrid_attn_fwd   one read-only denoising pass:
+ *                            out = softmax(q k^T * sm_scale) v  +  g * L2Norm(q) S
+ *                          (intra-chunk softmax branch Eq. (2); feature map Eq. (3);
+ *                           linear readout of the shared pre-update state Eq. (5), (7);
+ *                           headwise gate broadcast over the head dimension Eq. (6)).
+ *                          S is never written by this call (Sec. 3.3, clean-pass update).
+ *
+ *   arl2_state_commit      once per chunk, after the last denoising pass:
+ *                            S <- gate * S + sum_i L2Norm(k_i)^T v_i
+ *                          (Eq. (4) with beta = 1 and without the delta-correction term;
+ *                           the gate multiplies the old state only).
+ *
+ * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
+ * the identity, so phi is the L2 normalisation over the head dimension,
+ * x / sqrt(sum x^2 + l2_eps), and V' = v.
+ *
+ * All data pointers are DEVICE pointers owned by the caller, 16-byte aligned and
+ * contiguous in the layouts below.  The library never allocates, frees or
+ * synchronises: every call validates its arguments on the host, enqueues its kernels
+ * on desc->stream and returns.  A call that returns an error has launched nothing.
+ *
+ * Layouts (row-major):
+ *   q, out      [B][Lq ][H][D]   io_dtype
+ *   k, v        [B][Lkv][H][D]   io_dtype
+ *   g           [B][Lq ][H]      g_dtype, values in [0,1]      (branch-mix gate, Eq. (6))
+ *   S           [B][H][D][D]     fp32, S[d_k][d_v]; readout contracts d_k
+ *   gate        [B][H]           fp32                          (forget gate alpha, Eq. (4))
+ */
+#ifndef ARL2_H
+#define ARL2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ARL2_OK = 0,
+    ARL2_ERR_INVALID_ARG = 1,   /* NULL/misaligned pointer, non-positive size, bad enum    */
+    ARL2_ERR_UNSUPPORTED = 2,   /* valid request outside what the kernels implement        */
+    ARL2_ERR_WORKSPACE = 3,     /* workspace missing or smaller than arl2_workspace_bytes  */
+    ARL2_ERR_DEVICE = 4         /* a HIP launch failed; see arl2_last_error()              */
+} arl2_status;
+
+typedef enum { ARL2_F32 = 0, ARL2_BF16 = 1 } arl2_dtype;
+
+typedef struct {
+    int32_t B;            /* independent streams, >= 1                                      */
+    int32_t H;            /* heads, >= 1                                                    */
+    int32_t Lq;           /* query tokens of the chunk, >= 1                                */
+    int32_t Lkv;          /* key/value tokens; must equal Lq when S != NULL or in commit.   */
+                          /* Lkv != Lq (any value >= 1) is allowed for pure softmax, S NULL */
+    int32_t D;            /* head dimension d_k = d_v: 64 or 128                            */
+    int32_t io_dtype;     /* arl2_dtype of q, k, v, out                                     */
+    int32_t g_dtype;      /* arl2_dtype of g (ignored when g == NULL)                       */
+    float sm_scale;       /* softmax logit scale; 0 selects 1/sqrt(D)   (Eq. (1))           */
+    float l2_eps;         /* epsilon inside L2Norm's square root; 0 selects 1e-6            */
+    void *workspace;      /* device scratch for arl2_state_commit, >= arl2_workspace_bytes  */
+    size_t workspace_bytes;
+    void *stream;         /* hipStream_t; NULL is the default stream                        */
+} arl2_desc;
+
+/* Device scratch that arl2_state_commit needs for this descriptor (token-split partial
+ * sums).  arl2_hybrid_attn_fwd needs none.  Returns 0 for an invalid descriptor.          */
+size_t arl2_workspace_bytes(const arl2_desc *desc);
+
+/*
+ * Read-only denoising pass (paper Eq. (2), (3), (5), (6), (7); Alg. 1 inner loop).
+ *   q, k, v   device, io_dtype, layouts above; not modified.
+ *   S         device fp32 [B][H][D][D], READ-ONLY; NULL means a zero state (pure softmax,
+ *             used for layers that keep softmax over a KV cache, Eq. (1) with every cached
+ *             token visible).
+ *   g         device [B][Lq][H]; NULL means a gate of one.
+ *   out       device, io_dtype [B][Lq][H][D]; fully overwritten; must not alias an input.
+ * bf16 I/O runs on bf16 MFMA with fp32 accumulation and fp32 softmax statistics;
+ * fp32 I/O runs in fp32 throughout.
+ */
+arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc,
+                                 const void *q, const void *k, const void *v,
+                                 const float *S, const void *g, void *out);
+
+/*
+ * Post-denoise state update (paper Eq. (3), Eq. (4); Alg. 1 clean pass).
+ *   k, v      device, io_dtype [B][Lq][H][D] of the clean pass (desc->Lkv must equal Lq).
+ *   gate      device fp32 [B][H].
+ *   S         device fp32 [B][H][D][D], updated IN PLACE.
+ * The token-split partial sums are reduced in a fixed order: results are bit-identical
+ * from run to run.  Uses desc->workspace.
+ */
+arl2_status arl2_state_commit(const arl2_desc *desc,
+                              const void *k, const void *v,
+                              const float *gate, float *S);
+
+const char *arl2_status_string(arl2_status s);
+
+/* Thread-local detail of the last failing call on this thread ("" if none). */
+const char *arl2_last_error(void);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int arl2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARL2_H */

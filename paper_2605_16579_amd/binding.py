@@ -1,0 +1,160 @@
+"""ctypes binding of the C ABI in ``include/arl2.h``: argument marshalling only.
+
+Every step of the hybrid attention path runs in the HIP kernels of ``libarl2_hip.so``;
+torch is used for device memory and streams.  There is no fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libarl2_hip.so")
+
+ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ERR_DEVICE = range(5)
+ARL2_F32, ARL2_BF16 = 0, 1
+
+EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit",
+           "arl2_status_string", "arl2_last_error", "arl2_version"]
+
+
+class arl2_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Lq", ctypes.c_int32),
+                ("Lkv", ctypes.c_int32), ("D", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("g_dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float), ("l2_eps", ctypes.c_float),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("stream", ctypes.c_void_p)]
+
+
+class Arl2Error(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name}: {detail}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built library (build it first with ``python -m paper_2605_16579_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -m paper_2605_16579_amd.build` (there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        dp = ctypes.POINTER(arl2_desc)
+        lib.arl2_workspace_bytes.argtypes = [dp]
+        lib.arl2_workspace_bytes.restype = ctypes.c_size_t
+        lib.arl2_hybrid_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        lib.arl2_hybrid_attn_fwd.restype = ctypes.c_int
+        lib.arl2_state_commit.argtypes = [dp, vp, vp, vp, vp]
+        lib.arl2_state_commit.restype = ctypes.c_int
+        lib.arl2_status_string.argtypes = [ctypes.c_int]
+        lib.arl2_status_string.restype = ctypes.c_char_p
+        lib.arl2_last_error.argtypes = []
+        lib.arl2_last_error.restype = ctypes.c_char_p
+        lib.arl2_version.argtypes = []
+        lib.arl2_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != ARL2_OK:
+        lib = load_library()
+        raise Arl2Error(status, lib.arl2_status_string(status).decode(), lib.arl2_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return ARL2_F32
+    if t.dtype == torch.bfloat16:
+        return ARL2_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: use float32 or bfloat16")
+
+
+def _dev(t: Optional[torch.Tensor], name: str, shape=None, dtype=None) -> Optional[int]:
+    """Device pointer of a contiguous CUDA/HIP tensor (None passes through as NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    return t.data_ptr()
+
+
+def make_desc(B, H, Lq, Lkv, D, io_dtype, g_dtype=ARL2_F32, sm_scale=0.0, l2_eps=0.0,
+              workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None) -> arl2_desc:
+    d = arl2_desc()
+    d.B, d.H, d.Lq, d.Lkv, d.D = B, H, Lq, Lkv, D
+    d.io_dtype, d.g_dtype = io_dtype, g_dtype
+    d.sm_scale, d.l2_eps = sm_scale, l2_eps
+    if workspace is not None:
+        d.workspace = _dev(workspace, "workspace")
+        d.workspace_bytes = workspace.numel() * workspace.element_size()
+    else:
+        d.workspace, d.workspace_bytes = None, 0
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+    d.stream = stream
+    return d
+
+
+def arl2_workspace_bytes(B: int, H: int, L: int, D: int, io_dtype) -> int:
+    """Device scratch bytes arl2_state_commit needs for this problem."""
+    code = io_dtype if isinstance(io_dtype, int) else (ARL2_BF16 if io_dtype == torch.bfloat16 else ARL2_F32)
+    d = make_desc(B, H, L, L, D, code, stream=0)
+    return int(load_library().arl2_workspace_bytes(ctypes.byref(d)))
+
+
+def arl2_hybrid_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                         S: Optional[torch.Tensor], g: Optional[torch.Tensor], out: torch.Tensor,
+                         *, sm_scale: float = 0.0, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """Read-only denoising pass, enqueued on the current (or given) stream; writes ``out``."""
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [B, L, H, D]")
+    B, Lq, H, D = q.shape
+    Lkv = k.shape[1]
+    io = _dtype_code(q)
+    d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
+                  stream=stream)
+    st = load_library().arl2_hybrid_attn_fwd(
+        ctypes.byref(d),
+        _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
+        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", (B, Lq, H)),
+        _dev(out, "out", (B, Lq, H, D), q.dtype))
+    _check(st)
+
+
+def arl2_state_commit(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor, S: torch.Tensor,
+                      workspace: torch.Tensor, *, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """Post-denoise update of ``S`` in place, enqueued on the current (or given) stream."""
+    if k.dim() != 4:
+        raise ValueError("k must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, workspace=workspace, stream=stream)
+    st = load_library().arl2_state_commit(
+        ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
+        _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
+    _check(st)
+
+
+def arl2_version() -> int:
+    return int(load_library().arl2_version())
+
+
+def alloc_workspace(B: int, H: int, L: int, D: int, dtype, device="cuda") -> torch.Tensor:
+    """Convenience: a torch buffer of arl2_workspace_bytes() bytes."""
+    n = arl2_workspace_bytes(B, H, L, D, dtype)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)

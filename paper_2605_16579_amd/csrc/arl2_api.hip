@@ -1,0 +1,129 @@
+// Host side of the C ABI declared in include/arl2.h: argument validation, dispatch to the
+// gfx950 kernels, error reporting.  Nothing here allocates device memory or synchronises.
+#include "../../include/arl2.h"
+#include "arl2_device.h"
+
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+arl2_status fail(arl2_status s, const char *fmt, const char *detail = "")
+{
+    std::snprintf(g_err, sizeof(g_err), fmt, detail);
+    return s;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks everything that does not depend on which call is made.
+arl2_status check_desc(const arl2_desc *d)
+{
+    if (d == nullptr) return fail(ARL2_ERR_INVALID_ARG, "desc is NULL");
+    if (d->B < 1 || d->H < 1 || d->Lq < 1 || d->Lkv < 1)
+        return fail(ARL2_ERR_INVALID_ARG, "B, H, Lq, Lkv must all be >= 1");
+    if (d->io_dtype != ARL2_F32 && d->io_dtype != ARL2_BF16)
+        return fail(ARL2_ERR_INVALID_ARG, "io_dtype is not an arl2_dtype");
+    if (d->g_dtype != ARL2_F32 && d->g_dtype != ARL2_BF16)
+        return fail(ARL2_ERR_INVALID_ARG, "g_dtype is not an arl2_dtype");
+    if (d->D != 64 && d->D != 128) return fail(ARL2_ERR_UNSUPPORTED, "D must be 64 or 128");
+    if (!(d->sm_scale >= 0.f) || !(d->l2_eps >= 0.f))
+        return fail(ARL2_ERR_INVALID_ARG, "sm_scale and l2_eps must be >= 0 (0 selects the default)");
+    // element counts must stay addressable with the kernels' index arithmetic
+    const double tokens = (double)d->B * (double)(d->Lq > d->Lkv ? d->Lq : d->Lkv);
+    if (tokens > 2.0e9 || (double)d->B * d->H > 1.0e6)
+        return fail(ARL2_ERR_UNSUPPORTED, "problem too large (B*L must stay below 2e9, B*H below 1e6)");
+    return ARL2_OK;
+}
+
+float resolved_eps(const arl2_desc *d) { return d->l2_eps > 0.f ? d->l2_eps : 1e-6f; }
+
+size_t commit_workspace(const arl2_desc *d)
+{
+    if (d->io_dtype == ARL2_BF16)
+        return (size_t)d->B * d->H * arl2::commit_nsplit(d->B, d->H, d->Lq) * d->D * d->D * sizeof(float);
+    return (size_t)d->B * d->Lq * d->H * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t arl2_workspace_bytes(const arl2_desc *desc)
+{
+    if (check_desc(desc) != ARL2_OK) return 0;
+    return commit_workspace(desc);
+}
+
+arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const void *k, const void *v,
+                                 const float *S, const void *g, void *out)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!q || !k || !v || !out) return fail(ARL2_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(S))
+        return fail(ARL2_ERR_INVALID_ARG, "q, k, v, S and out must be 16-byte aligned");
+    if (g && (reinterpret_cast<uintptr_t>(g) & 3u))
+        return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
+    if (out == q || out == k || out == v) return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
+    if (S != nullptr && desc->Lkv != desc->Lq)
+        return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
+
+    arl2::FwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.S = S; a.g = (S != nullptr) ? g : nullptr; a.out = out;
+    a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
+    a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
+    a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
+    a.l2_eps = resolved_eps(desc);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(desc->stream);
+    const hipError_t e = desc->io_dtype == ARL2_BF16 ? arl2::launch_fwd_bf16(a, stream)
+                                                     : arl2::launch_fwd_f32(a, stream);
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "fwd launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
+arl2_status arl2_state_commit(const arl2_desc *desc, const void *k, const void *v, const float *gate, float *S)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!k || !v || !gate || !S) return fail(ARL2_ERR_INVALID_ARG, "k, v, gate and S must not be NULL");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(S))
+        return fail(ARL2_ERR_INVALID_ARG, "k, v and S must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(gate) & 3u) return fail(ARL2_ERR_INVALID_ARG, "gate must be 4-byte aligned");
+    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in arl2_state_commit");
+    const size_t need = commit_workspace(desc);
+    if (desc->workspace == nullptr || desc->workspace_bytes < need)
+        return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
+    if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+
+    arl2::CommitArgs a;
+    a.k = k; a.v = v; a.gate = gate; a.S = S; a.workspace = desc->workspace;
+    a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.D = desc->D;
+    a.nsplit = arl2::commit_nsplit(desc->B, desc->H, desc->Lq);
+    a.l2_eps = resolved_eps(desc);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(desc->stream);
+    const hipError_t e = desc->io_dtype == ARL2_BF16 ? arl2::launch_commit_bf16(a, stream)
+                                                     : arl2::launch_commit_f32(a, stream);
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "commit launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
+const char *arl2_status_string(arl2_status s)
+{
+    switch (s) {
+    case ARL2_OK: return "ARL2_OK";
+    case ARL2_ERR_INVALID_ARG: return "ARL2_ERR_INVALID_ARG";
+    case ARL2_ERR_UNSUPPORTED: return "ARL2_ERR_UNSUPPORTED";
+    case ARL2_ERR_WORKSPACE: return "ARL2_ERR_WORKSPACE";
+    case ARL2_ERR_DEVICE: return "ARL2_ERR_DEVICE";
+    }
+    return "ARL2_ERR_UNKNOWN";
+}
+
+const char *arl2_last_error(void) { return g_err; }
+
+int arl2_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal declarations shared by the gfx950 kernels of the ARL^2 hybrid attention library.
+// Not part of the public interface (that is include/arl2.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace arl2 {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// MI355X has 8 accelerator dies (XCDs), each with its own L2; the hardware deals
+// consecutive workgroup ids to the XCDs round-robin.
+constexpr int kNumXcd = 8;
+constexpr int kWave = 64;
+
+struct FwdArgs {
+    const void *q, *k, *v;
+    const float *S;        // may be nullptr
+    const void *g;         // may be nullptr
+    void *out;
+    int B, H, Lq, Lkv, D;
+    int g_is_bf16;
+    float sm_scale;        // already resolved (never 0)
+    float l2_eps;          // already resolved
+};
+
+struct CommitArgs {
+    const void *k, *v;
+    const float *gate;
+    float *S;
+    void *workspace;
+    int B, H, L, D;
+    int nsplit;            // token splits per (stream, head) for the bf16 path
+    float l2_eps;
+};
+
+// Token splits used by the bf16 commit for a problem size (also sizes the workspace).
+int commit_nsplit(int B, int H, int L);
+
+// Launchers: enqueue on `stream`, return the HIP error of the launch.
+hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream);
+hipError_t launch_fwd_f32(const FwdArgs &a, hipStream_t stream);
+hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream);
+hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream);
+
+// ---- small device helpers -------------------------------------------------------------
+
+// Sum / max of a value held by lane l and lane l^32 (the two half-waves).
+__device__ __forceinline__ float xhalf_sum(float x)
+{
+    return x + __shfl_xor(x, 32, kWave);
+}
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    return fmaxf(x, __shfl_xor(x, 32, kWave));
+}
+
+// Round-to-nearest-even fp32 -> bf16 (hardware conversion on gfx950).
+__device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)x; }
+
+// Map the hardware workgroup id to a logical work index such that consecutive logical
+// indices run on the same XCD (and so share that XCD's L2).
+__device__ __forceinline__ int xcd_contiguous_id(int id, int n)
+{
+    const int per = n / kNumXcd, rem = n % kNumXcd;
+    const int x = id % kNumXcd, loc = id / kNumXcd;
+    return x * per + (x < rem ? x : rem) + loc;
+}
+
+}  // namespace arl2

@@ -1,0 +1,99 @@
+"""Host-side behaviour of the C ABI that needs no GPU: the library loads, exports every declared
+symbol, validates arguments before any launch and reports errors as status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2605_16579_amd as A
+    if not os.path.exists(A.binding.LIB_PATH):
+        from paper_2605_16579_amd import build
+        build.build()
+    A.load_library()
+    return A
+
+
+def test_every_declared_symbol_is_exported(A):
+    header = open(os.path.join(ROOT, "include", "arl2.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(arl2_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(A.binding.EXPORTS), declared ^ set(A.binding.EXPORTS)
+    lib = A.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_desc_struct_matches_header(A):
+    header = open(os.path.join(ROOT, "include", "arl2.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} arl2_desc;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = re.findall(r"\b(\w+)\s*;", body)
+    assert names == [f[0] for f in A.arl2_desc._fields_]
+    assert ctypes.sizeof(A.arl2_desc) == 64
+
+
+def test_status_strings_and_version(A):
+    lib = A.load_library()
+    assert lib.arl2_status_string(0) == b"ARL2_OK"
+    assert lib.arl2_status_string(3) == b"ARL2_ERR_WORKSPACE"
+    assert A.arl2_version() >= 100
+
+
+def test_workspace_bytes(A):
+    assert A.arl2_workspace_bytes(1, 2, 64, 64, A.ARL2_F32) == 1 * 64 * 2 * 4
+    n = A.arl2_workspace_bytes(1, 12, 4680, 128, A.ARL2_BF16)
+    assert n > 0 and n % (12 * 128 * 128 * 4) == 0
+    d = A.make_desc(1, 2, 64, 64, 96, A.ARL2_BF16, stream=0)      # unsupported head dim
+    assert A.load_library().arl2_workspace_bytes(ctypes.byref(d)) == 0
+
+
+def _fwd(A, d, q=0x1000, k=0x2000, v=0x3000, S=0x4000, g=0x5000, out=0x6000):
+    # the pointers are never dereferenced: every call below must fail validation before any launch
+    return A.load_library().arl2_hybrid_attn_fwd(ctypes.byref(d), q, k, v, S, g, out)
+
+
+def test_fwd_rejects_bad_arguments_before_launch(A):
+    lib = A.load_library()
+    ok = dict(B=1, H=2, Lq=64, Lkv=64, D=64, io_dtype=A.ARL2_BF16)
+    assert lib.arl2_hybrid_attn_fwd(None, 1, 1, 1, 1, 1, 1) == 1
+    for bad in (dict(B=0), dict(H=-1), dict(Lq=0), dict(Lkv=0), dict(io_dtype=7)):
+        d = A.make_desc(**{**ok, **bad}, stream=0)
+        assert _fwd(A, d) == 1, bad
+    assert _fwd(A, A.make_desc(**{**ok, "D": 80}, stream=0)) == 2
+    d = A.make_desc(**ok, stream=0)
+    assert _fwd(A, d, q=None) == 1
+    assert _fwd(A, d, out=None) == 1
+    assert _fwd(A, d, q=0x1004) == 1                      # misaligned
+    assert _fwd(A, d, out=0x1000) == 1                    # out aliases q
+    d2 = A.make_desc(**{**ok, "Lkv": 128}, stream=0)
+    assert _fwd(A, d2) == 1                               # Lkv != Lq with a state
+    assert b"Lkv" in lib.arl2_last_error()
+    d3 = A.make_desc(**ok, sm_scale=-1.0, stream=0)
+    assert _fwd(A, d3) == 1
+
+
+def test_commit_rejects_bad_arguments_before_launch(A):
+    lib = A.load_library()
+    d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    call = lambda d, k=0x1000, v=0x2000, gate=0x3000, S=0x4000: lib.arl2_state_commit(ctypes.byref(d), k, v, gate, S)
+    assert call(d) == 3                                   # no workspace
+    d.workspace, d.workspace_bytes = 0x10000, 16
+    assert call(d) == 3                                   # too small
+    d.workspace_bytes = A.arl2_workspace_bytes(1, 2, 64, 64, A.ARL2_BF16)
+    assert call(d, S=None) == 1
+    assert call(d, gate=0x3002) == 1
+    d.Lkv = 32
+    assert call(d) == 1
+
+
+def test_binding_refuses_host_tensors(A):
+    import torch
+    q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        A.arl2_hybrid_attn_fwd(q, q, q, None, None, torch.empty_like(q))

@@ -1,0 +1,239 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the CPU oracle,
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from helpers import (TOL_BF16_OUT, TOL_F32, TOL_STATE, rel_err, rel_err_per_head, sample_rows, to_np)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_16579_amd as A
+    A.load_library()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return A
+
+
+def dev(t):
+    return t.cuda() if t is not None else None
+
+
+def gpu_fwd(A, q, k, v, S, g):
+    out = torch.empty_like(q, device="cuda")
+    A.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(g), out)
+    torch.cuda.synchronize()
+    return out
+
+
+def gpu_commit(A, k, v, gate, S_dev):
+    B, L, H, D = k.shape
+    ws = A.alloc_workspace(B, H, L, D, k.dtype)
+    A.arl2_state_commit(dev(k), dev(v), dev(gate), S_dev, ws)
+    torch.cuda.synchronize()
+
+
+def run_rollout_parity(A, oracle, w, tol_out, tol_state, precision="f64", seed=0):
+    """Alg. 1 call pattern on workload w: every pass output and every committed state is compared."""
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    for j in range(w.prefill):
+        k, v, gate = W.prefill_inputs(w, j, seed)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+        gpu_commit(A, k, v, gate, S_dev)
+    worst_out = worst_state = 0.0
+    for c in range(w.chunks):
+        S_before = S_dev.clone()
+        for p in range(w.passes):
+            q, k, v, g = W.pass_inputs(w, c, p, seed)
+            # the oracle reads the state the GPU actually holds (fp32), widened exactly
+            ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g))
+            got = gpu_fwd(A, q, k, v, S_dev, g)
+            e = rel_err(to_np(got), ref)
+            worst_out = max(worst_out, e)
+            assert e <= tol_out, f"{w.name} chunk {c} pass {p}: out error {e:.3e}"
+            assert torch.equal(S_dev, S_before), "a readout pass wrote the state"
+        k, v, gate = W.clean_inputs(w, c, seed)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)   # fp64 chain, never re-synced to the GPU
+        gpu_commit(A, k, v, gate, S_dev)
+        assert not torch.equal(S_dev, S_before), "commit left the state unchanged"
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        worst_state = max(worst_state, e)
+        assert e <= tol_state, f"{w.name} chunk {c}: state error {e:.3e}"
+    print(f"[{w.name}] worst out err {worst_out:.3e}, worst state err {worst_state:.3e}", flush=True)
+
+
+def test_tiny_fp32_rollout(lib, oracle):
+    run_rollout_parity(lib, oracle, W.WORKLOADS["tiny"], TOL_F32, TOL_F32)
+
+
+def test_ragged_small_bf16_rollout(lib, oracle):
+    run_rollout_parity(lib, oracle, W.WORKLOADS["ragged_small"], TOL_BF16_OUT, TOL_STATE)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_other_head_dims(lib, oracle, D, io):
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"hd{D}{io}", D=D, io_dtype=io, L=200, chunks=2)
+    tol_o, tol_s = (TOL_BF16_OUT, TOL_STATE) if io == "bf16" else (TOL_F32, TOL_F32)
+    run_rollout_parity(lib, oracle, w, tol_o, tol_s)
+
+
+@pytest.mark.parametrize("L", [1, 7, 63, 64, 65, 127, 128, 129, 191, 256, 333])
+def test_branches_separately_and_ragged_lengths(lib, oracle, L):
+    """Each branch alone (the linear branch is ~100x larger with these inputs and would hide an
+    intra-branch error in a combined max-norm check), for lengths around the tile edges."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"len{L}", L=L, B=1, H=2)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    kc, vc, gate = W.clean_inputs(w, 0)
+    S = torch.from_numpy(oracle.commit(to_np(kc), to_np(vc), to_np(gate), np.zeros((w.B, w.H, w.D, w.D)))).float()
+    # intra alone: no state
+    e = rel_err(to_np(gpu_fwd(lib, q, k, v, None, None)), oracle.fwd(to_np(q), to_np(k), to_np(v)))
+    assert e <= TOL_BF16_OUT, f"intra L={L}: {e:.3e}"
+    # inter alone: v = 0 makes the softmax branch vanish
+    vz = torch.zeros_like(v)
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(vz), to_np(S).astype(np.float64), to_np(g))
+    e = rel_err(to_np(gpu_fwd(lib, q, k, vz, S, g)), ref)
+    assert e <= TOL_BF16_OUT, f"inter L={L}: {e:.3e}"
+    # gate of one (g == NULL) and gate of zero
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), None)
+    assert rel_err(to_np(gpu_fwd(lib, q, k, v, S, None)), ref) <= TOL_BF16_OUT
+    g0 = torch.zeros_like(g)
+    assert torch.equal(gpu_fwd(lib, q, k, v, S, g0), gpu_fwd(lib, q, k, v, None, None))
+    # bf16 gate tensor
+    gb = g.to(torch.bfloat16)
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(gb))
+    assert rel_err(to_np(gpu_fwd(lib, q, k, v, S, gb)), ref) <= TOL_BF16_OUT
+    # commit at this length
+    S_dev = S.cuda()
+    gpu_commit(lib, k, v, gate, S_dev)
+    ref = oracle.commit(to_np(k), to_np(v), to_np(gate), to_np(S).astype(np.float64))
+    assert rel_err_per_head(to_np(S_dev), ref) <= TOL_STATE
+
+
+@pytest.mark.parametrize("Lq,Lkv", [(100, 300), (128, 64), (1, 500), (200, 1)])
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_softmax_over_longer_kv(lib, oracle, Lq, Lkv, io):
+    """S == NULL with Lkv != Lq: softmax over a KV cache in which every cached token is visible."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="kvcache", io_dtype=io)
+    q = W.normal(1, w, (w.B, Lq, w.H, w.D), 1)
+    k = W.normal(1, w, (w.B, Lkv, w.H, w.D), 2)
+    v = W.normal(1, w, (w.B, Lkv, w.H, w.D), 3)
+    got = gpu_fwd(lib, q, k, v, None, None)
+    e = rel_err(to_np(got), oracle.fwd(to_np(q), to_np(k), to_np(v)))
+    assert e <= (TOL_BF16_OUT if io == "bf16" else TOL_F32), f"{e:.3e}"
+
+
+def test_peaked_softmax_and_large_logits(lib, oracle):
+    """Rows whose maximum moves late in the key sequence and logits of a few hundred: the running-max
+    rescale must stay exact and finite."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="peaked", B=1, H=2, L=300)
+    q, k, v, _ = W.pass_inputs(w, 0, 0)
+    k = k.float()
+    k[:, 250:260] *= 8.0          # large keys near the end
+    q = (q.float() * 3.0).to(torch.bfloat16)
+    k = k.to(torch.bfloat16)
+    got = gpu_fwd(lib, q, k, v, None, None)
+    e = rel_err(to_np(got), oracle.fwd(to_np(q), to_np(k), to_np(v)))
+    assert e <= TOL_BF16_OUT, f"{e:.3e}"
+
+
+def test_commit_is_deterministic_and_fwd_repeatable(lib):
+    w = W.WORKLOADS["ragged_small"]
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    kc, vc, gate = W.clean_inputs(w, 0)
+    S0 = torch.randn((w.B, w.H, w.D, w.D), generator=torch.Generator().manual_seed(3))
+    results = []
+    for _ in range(3):
+        S_dev = S0.cuda()
+        gpu_commit(lib, kc, vc, gate, S_dev)
+        results.append(S_dev.clone())
+    assert torch.equal(results[0], results[1]) and torch.equal(results[0], results[2])
+    o1 = gpu_fwd(lib, q, k, v, S0, g)
+    o2 = gpu_fwd(lib, q, k, v, S0, g)
+    assert torch.equal(o1, o2)
+
+
+def test_wan_layer_full_size(lib, oracle):
+    """The headline shape (12 heads x 128, 4680 tokens): state pre-filled by 8 oracle commits, four
+    readout passes checked on sampled rows (each row depends only on its own q and all of k, v, S),
+    then one commit checked in full."""
+    w = W.WORKLOADS["wan_layer"]
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    for j in range(w.prefill):
+        k, v, gate = W.prefill_inputs(w, j)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+        gpu_commit(lib, k, v, gate, S_dev)
+    e = rel_err_per_head(to_np(S_dev), S_ref)
+    print(f"[wan_layer] state after 8 prefill commits: {e:.3e}", flush=True)
+    assert e <= TOL_STATE
+    S_before = S_dev.clone()
+    for p in range(w.passes):
+        q, k, v, g = W.pass_inputs(w, 0, p)
+        rows = sample_rows(w.L, 256, seed=p)
+        S64 = to_np(S_dev).astype(np.float64)
+        got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
+        e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g), rows=rows))
+        # intra branch alone on the same rows
+        got_i = to_np(gpu_fwd(lib, q, k, v, None, None))[:, rows]
+        ei = rel_err(got_i, oracle.fwd(to_np(q), to_np(k), to_np(v), rows=rows))
+        print(f"[wan_layer] pass {p}: out {e:.3e}  intra-only {ei:.3e}  ({len(rows)} rows/head)", flush=True)
+        assert e <= TOL_BF16_OUT and ei <= TOL_BF16_OUT
+        assert torch.equal(S_dev, S_before)
+    k, v, gate = W.clean_inputs(w, 0)
+    S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+    gpu_commit(lib, k, v, gate, S_dev)
+    e = rel_err_per_head(to_np(S_dev), S_ref)
+    print(f"[wan_layer] state after the chunk's commit: {e:.3e}", flush=True)
+    assert e <= TOL_STATE
+
+
+def test_wan_batched_full_size(lib, oracle):
+    """8 streams at the headline shape: sampled rows of one pass, full state after one commit."""
+    w = W.WORKLOADS["wan_batched"]
+    kc, vc, gate = W.prefill_inputs(w, 0)
+    S_ref = oracle.commit(to_np(kc), to_np(vc), to_np(gate), np.zeros((w.B, w.H, w.D, w.D)))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    gpu_commit(lib, kc, vc, gate, S_dev)
+    e = rel_err_per_head(to_np(S_dev), S_ref)
+    print(f"[wan_batched] state after one commit: {e:.3e}", flush=True)
+    assert e <= TOL_STATE
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    rows = sample_rows(w.L, 24, seed=7)
+    got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
+    e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g), rows=rows))
+    print(f"[wan_batched] out: {e:.3e}", flush=True)
+    assert e <= TOL_BF16_OUT
+
+
+def test_wan_rollout_64_chained_commits(lib, oracle):
+    """State drift over 64 chained commits at the headline shape against the fp64 oracle chain,
+    with readout rows checked on the first, a middle and the last chunk."""
+    w = W.WORKLOADS["wan_rollout"]
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    worst = 0.0
+    for c in range(w.chunks):
+        if c in (0, 31, 63):
+            q, k, v, g = W.pass_inputs(w, c, 0)
+            rows = sample_rows(w.L, 32, seed=c)
+            got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
+            e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g), rows=rows))
+            assert e <= TOL_BF16_OUT, f"chunk {c}: out {e:.3e}"
+        k, v, gate = W.clean_inputs(w, c)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+        gpu_commit(lib, k, v, gate, S_dev)
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        worst = max(worst, e)
+        if c % 8 == 7:
+            print(f"[wan_rollout] chunk {c}: state err {e:.3e}", flush=True)
+        assert e <= TOL_STATE, f"chunk {c}: state {e:.3e}"
+    print(f"[wan_rollout] worst state err over 64 chained commits {worst:.3e}", flush=True)
