@@ -11,8 +11,13 @@
 // With v_mfma_f32_32x32x16_bf16 a lane holds one query column (lane % 32) of the S^T
 // accumulator, so the softmax row statistics are in-lane reductions plus one exchange
 // between the two half-waves.  The accumulator registers of S^T are exactly a B operand of
-// the second GEMM for a permuted key order; V^T is written to LDS in that same permuted
-// order (key index bits 2 and 3 swapped inside each group of 16 keys).
+// the second GEMM (k-slot j of half-wave hh is key 16t + 8(j/4) + 4hh + j%4); the matching
+// V^T fragments come from the row-major V tile in LDS through the transposing LDS read
+// (ds_read_b64_tr_b16), four keys per read.
+//
+// K/V tiles are double-buffered in LDS (one barrier per tile); the running maximum is only
+// raised when a row's tile maximum exceeds it by more than 2^8, which removes the
+// accumulator rescale from almost every tile without changing the normalised result.
 //
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
 // state split into bf16 hi + lo parts staged through the (now free) K/V LDS, the raw bf16 q
@@ -32,10 +37,11 @@ struct FwdCfg {
     static constexpr int DB = D / 32;            // 32-row blocks of O^T
     static constexpr int CPR = D / 8;            // 16-byte chunks per row
     static constexpr int KROW = 2 * D + 16;      // LDS bytes per K row (padded: conflict-free b128 reads)
-    static constexpr int VROW = 2 * BN + 8;      // LDS bytes per V^T row (padded: conflict-free b64 reads)
+    static constexpr int VROW = 2 * D + 64;      // LDS bytes per V row (padded: conflict-free transposing reads)
     static constexpr int K_BYTES = BN * KROW;
-    static constexpr int V_BYTES = D * VROW;
-    static constexpr int KV_BYTES = K_BYTES + V_BYTES;
+    static constexpr int V_BYTES = BN * VROW;
+    static constexpr int STAGE = K_BYTES + V_BYTES;   // one K/V tile
+    static constexpr int KV_BYTES = 2 * STAGE;        // double-buffered
     static constexpr int ST_BYTES = D * KROW;    // state staging [e][d]
     static constexpr int OUT_BYTES = BM * KROW;  // output staging [q][e]
     static constexpr int SMEM = (KV_BYTES > ST_BYTES ? (KV_BYTES > OUT_BYTES ? KV_BYTES : OUT_BYTES)
@@ -43,10 +49,16 @@ struct FwdCfg {
     static constexpr int KCH = BN * CPR / NT;    // K chunks per thread per tile
 };
 
-// Position of key (kv mod 64) inside a V^T row: swap bits 2 and 3.
-__device__ __forceinline__ int vt_pos(int kvl)
+// Raise the running maximum only when the tile maximum exceeds it by more than this (log2 units).
+constexpr float kRescaleThreshold = 8.0f;
+
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+// Transposing LDS read: within each group of 16 lanes, lane i receives element i of the four
+// 16-element rows whose 8-byte pieces are addressed by lanes 4j..4j+3 (j = 0..3).
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p)
 {
-    return (kvl & ~12) | ((kvl & 4) << 1) | ((kvl & 8) >> 1);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
 }
 
 template <int D>
@@ -54,8 +66,6 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 {
     using C = FwdCfg<D>;
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];
-    unsigned char *smK = smem;
-    unsigned char *smV = smem + C::K_BYTES;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, c = lane & 31, hh = lane >> 5;
@@ -92,53 +102,38 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         qss = xhalf_sum(qss);   // |q_row|^2 over the full head dimension
     }
 
-    // ---- per-thread roles for the global -> LDS copies
-    // K: 16-byte chunks, chunk id = tid + NT*i -> (row, col)
-    // V: one 4-key x 8-dim block per thread, transposed in registers
-    const int v_dg = tid % C::CPR, v_u = tid / C::CPR;
-    const bool v_active = v_u < BN / 4;
-    const int v_p0 = vt_pos(4 * v_u);
-
+    // ---- global -> LDS copies: 16-byte chunks, chunk id = tid + NT*i -> (row, col), for K and V alike
     u32x4 kreg[C::KCH];
-    u32x4 vreg[4];
+    u32x4 vreg[C::KCH];
+
+    // transposing-read role of this lane: row offset and byte offset inside a 32-column block
+    const int tr_row = ((lane & 15) >> 2) + 4 * hh;
+    const int tr_col = 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
 
     auto load_tile = [&](int kv0) {
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
             const int id = tid + NT * i;
             const int row = id / C::CPR, col = id % C::CPR;
-            u32x4 x = {0, 0, 0, 0};
-            if (kv0 + row < Lkv) x = *(const u32x4 *)(kg + (size_t)(kv0 + row) * tok_stride + 8 * col);
-            kreg[i] = x;
-        }
-        if (v_active) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int kv = kv0 + 4 * v_u + e;
-                u32x4 x = {0, 0, 0, 0};
-                if (kv < Lkv) x = *(const u32x4 *)(vg + (size_t)kv * tok_stride + 8 * v_dg);
-                vreg[e] = x;
+            u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
+            if (kv0 + row < Lkv) {
+                x = *(const u32x4 *)(kg + (size_t)(kv0 + row) * tok_stride + 8 * col);
+                y = *(const u32x4 *)(vg + (size_t)(kv0 + row) * tok_stride + 8 * col);
             }
+            kreg[i] = x;
+            vreg[i] = y;
         }
     };
 
-    auto store_tile = [&]() {
+    auto store_tile = [&](int stage) {
+        unsigned char *smK = smem + stage * C::STAGE;
+        unsigned char *smV = smK + C::K_BYTES;
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
             const int id = tid + NT * i;
             const int row = id / C::CPR, col = id % C::CPR;
             *(u32x4 *)(smK + row * C::KROW + 16 * col) = kreg[i];
-        }
-        if (v_active) {
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                const int w = m >> 1;
-                const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
-                u32x2 o;
-                o[0] = __builtin_amdgcn_perm(vreg[1][w], vreg[0][w], sel);
-                o[1] = __builtin_amdgcn_perm(vreg[3][w], vreg[2][w], sel);
-                *(u32x2 *)(smV + (8 * v_dg + m) * C::VROW + 2 * v_p0) = o;
-            }
+            *(u32x4 *)(smV + row * C::VROW + 16 * col) = vreg[i];
         }
     };
 
@@ -153,13 +148,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 
     const int ntiles = (Lkv + BN - 1) / BN;
     load_tile(0);
+    store_tile(0);
+    __syncthreads();
 
     for (int it = 0; it < ntiles; ++it) {
         const int kv0 = it * BN;
-        __syncthreads();            // all waves are done reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (it + 1 < ntiles) load_tile(kv0 + BN);
+        const unsigned char *smK = smem + (it & 1) * C::STAGE;
+        const unsigned char *smV = smK + C::K_BYTES;
+        if (it + 1 < ntiles) load_tile(kv0 + BN);   // lands in registers while this tile is computed
 
         // S^T = K Q^T for two 32-key blocks
         f32x16 s[2];
@@ -189,24 +185,27 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-        mx = xhalf_max(mx);
-        const float m_new = fmaxf(m_run, mx * scale_log2);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        mx = xhalf_max(mx) * scale_log2;
+        if (__any(mx > m_run + kRescaleThreshold)) {      // wave-uniform: rare after the first tiles
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+        }
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -m_new));
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -m_run));
                 s[kb][r] = pv;
                 psum += pv;
             }
-        l_run = fmaf(l_run, alpha, psum);
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+        l_run += psum;
 
         // P^T fragments: accumulator registers 8*(t&1)..+7 of block t/2 are one B operand
         bf16x8 pf[4];
@@ -220,13 +219,15 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         for (int db = 0; db < C::DB; ++db) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const unsigned char *vp = smV + (32 * db + c) * C::VROW + 32 * t + 16 * hh;
-                union { u32x2 u[2]; bf16x8 v; } va;
-                va.u[0] = *(const u32x2 *)(vp);
-                va.u[1] = *(const u32x2 *)(vp + 8);
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pf[t], o_acc[db], 0, 0, 0);
+                const unsigned char *vp = smV + (16 * t + tr_row) * C::VROW + 64 * db + tr_col;
+                const bf16x4 lo = lds_read_tr(vp);                    // keys 16t + 4hh + 0..3
+                const bf16x4 hi = lds_read_tr(vp + 8 * C::VROW);      // keys 16t + 8 + 4hh + 0..3
+                const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[t], o_acc[db], 0, 0, 0);
             }
         }
+        if (it + 1 < ntiles) store_tile((it + 1) & 1);   // the other buffer was last read one tile ago
+        __syncthreads();
     }
 
     // ---- epilogue ------------------------------------------------------------------------
