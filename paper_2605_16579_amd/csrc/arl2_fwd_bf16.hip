@@ -1,12 +1,12 @@
 // Read-only denoising pass on bf16 MFMA (gfx950):
 //   out = softmax(q k^T * sm_scale) v + g * L2Norm(q) S            paper Eq. (2), (3), (5), (6)
 //
-// One workgroup (4 wavefronts) owns 128 query rows of one (stream, head); each wavefront owns
-// 32 of them.  Everything is computed transposed so that no operand ever has to be re-laid
-// out between the two GEMMs:
+// One workgroup (8 wavefronts, two per SIMD, 256 registers each) owns 256 query rows of one
+// (stream, head); each wavefront owns 32 of them.  Everything is computed transposed so that
+// no operand is re-laid out between the two GEMMs:
 //
 //   S^T[kv][q]  = K[kv][:] . Q[q][:]      A = K tile rows from LDS,  B = Q fragments in registers
-//   O^T[d][q]  += V^T[d][kv] . P^T[kv][q] A = V^T tile rows from LDS, B = exp'd S^T accumulators
+//   O^T[d][q]  += V^T[d][kv] . P^T[kv][q] A = V^T fragments from LDS, B = exp'd S^T accumulators
 //
 // With v_mfma_f32_32x32x16_bf16 a lane holds one query column (lane % 32) of the S^T
 // accumulator, so the softmax row statistics are in-lane reductions plus one exchange
@@ -15,21 +15,39 @@
 // V^T fragments come from the row-major V tile in LDS through the transposing LDS read
 // (ds_read_b64_tr_b16), four keys per read.
 //
-// K/V tiles are double-buffered in LDS (one barrier per tile); the running maximum is only
-// raised when a row's tile maximum exceeds it by more than 2^8, which removes the
-// accumulator rescale from almost every tile without changing the normalised result.
+// A wavefront cannot overlap its own VALU work with its own MFMAs on this hardware, but the
+// two wavefronts that share a SIMD can overlap each other.  The wavefronts of a workgroup
+// therefore run the same per-tile work in two rotations, half a tile apart:
+//
+//   wavefronts 0-3:   S(i)        softmax(i)   PV(i)      | barrier
+//   wavefronts 4-7:   softmax(i)  PV(i)        S(i+1)     | barrier
+//
+// so the softmax arithmetic of one group is issued while the other group keeps the matrix
+// cores busy.  Inside an MFMA chain every step issues one MFMA and the LDS read of the operand
+// fragment needed several MFMAs later.
+//
+// K/V tiles travel HBM/L2 -> registers (buffer loads, zero beyond the last key) -> a 3-stage
+// LDS ring with one workgroup barrier per tile.  The running maximum is only raised when a
+// row's tile maximum exceeds it by more than 2^8, which removes the accumulator rescale from
+// almost every tile without changing the normalised result.  Row sums are taken over the
+// bf16-rounded probabilities that the second GEMM actually multiplies.
 //
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
-// state split into bf16 hi + lo parts staged through the (now free) K/V LDS, the raw bf16 q
+// state split into bf16 hi + lo parts staged through the (now free) LDS, the raw bf16 q
 // fragments as B operand, and the L2 norm of q applied as an fp32 per-column scale.
 #include "arl2_device.h"
+
+#include <type_traits>
 
 namespace arl2 {
 namespace {
 
-constexpr int BM = 128;   // query rows per workgroup
+constexpr int BM = 256;   // query rows per workgroup
 constexpr int BN = 64;    // keys per tile
-constexpr int NT = 256;   // threads per workgroup
+constexpr int NT = 512;   // threads per workgroup
+constexpr int NSTAGE = 3; // LDS ring depth
+constexpr int PF = 7;     // operand fragments are read from LDS this many MFMAs ahead
+constexpr int RING = 8;   // fragment registers (PF + 1)
 
 template <int D>
 struct FwdCfg {
@@ -41,12 +59,17 @@ struct FwdCfg {
     static constexpr int K_BYTES = BN * KROW;
     static constexpr int V_BYTES = BN * VROW;
     static constexpr int STAGE = K_BYTES + V_BYTES;   // one K/V tile
-    static constexpr int KV_BYTES = 2 * STAGE;        // double-buffered
+    static constexpr int KV_BYTES = NSTAGE * STAGE;
     static constexpr int ST_BYTES = D * KROW;    // state staging [e][d]
     static constexpr int OUT_BYTES = BM * KROW;  // output staging [q][e]
     static constexpr int SMEM = (KV_BYTES > ST_BYTES ? (KV_BYTES > OUT_BYTES ? KV_BYTES : OUT_BYTES)
                                                      : (ST_BYTES > OUT_BYTES ? ST_BYTES : OUT_BYTES));
-    static constexpr int KCH = BN * CPR / NT;    // K chunks per thread per tile
+    static constexpr int KCH = BN * CPR / NT;    // 16-byte chunks per thread per tile (K and V each)
+    static constexpr int ROWS_PER_PASS = NT / CPR;
+    static constexpr int S_LEN = 2 * KS;         // MFMAs of one S^T chain (two 32-key blocks)
+    static constexpr int PV_LEN = 4 * DB;        // MFMAs of one PV chain
+    static_assert(KCH >= 1, "tile too small for the workgroup");
+    static_assert(S_LEN % RING == 0 && PV_LEN % RING == 0, "chain lengths must be multiples of the fragment ring");
 };
 
 // Raise the running maximum only when the tile maximum exceeds it by more than this (log2 units).
@@ -61,6 +84,21 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
 }
 
+// Raw buffer descriptor over [base, base + bytes): loads beyond the range return zero.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2)
 {
@@ -69,6 +107,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, c = lane & 31, hh = lane >> 5;
+    const int group = wave >> 2;      // 0: S, softmax, PV per barrier interval; 1: softmax, PV, next S
 
     const int work = xcd_contiguous_id(blockIdx.x, gridDim.x);
     const int qt = work % n_qtiles;
@@ -79,11 +118,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     const bf16_t *qg = (const bf16_t *)a.q;
     const bf16_t *kg = (const bf16_t *)a.k + ((size_t)b * Lkv * H + h) * D;
     const bf16_t *vg = (const bf16_t *)a.v + ((size_t)b * Lkv * H + h) * D;
-    const size_t tok_stride = (size_t)H * D;
+    const uint32_t tok_bytes = (uint32_t)H * D * 2;                       // one token, all heads
+    const uint32_t kv_range = (uint32_t)(Lkv - 1) * tok_bytes + 2 * D;    // bytes of this head's K (or V) slice
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(kg, kv_range);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(vg, kv_range);
 
-    // ---- Q fragments (B operand of S^T = K Q^T): lane (c, hh) holds Q[row c][16 t + 8 hh + 0..7]
-    const int q0 = qt * BM;
-    const int qrow = q0 + wave * 32 + c;
+    // ---- Q fragments (B operand of S^T = K Q^T): lane (c, hh) holds Q[row][16 t + 8 hh + 0..7]
+    const int q0 = qt * BM + wave * 32;
+    const int qrow = q0 + c;
     bf16x8 qf[C::KS];
     float qss = 0.f;
     {
@@ -102,89 +144,104 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         qss = xhalf_sum(qss);   // |q_row|^2 over the full head dimension
     }
 
-    // ---- global -> LDS copies: 16-byte chunks, chunk id = tid + NT*i -> (row, col), for K and V alike
-    u32x4 kreg[C::KCH];
-    u32x4 vreg[C::KCH];
+    // ---- global -> registers -> LDS copies: 16-byte chunks, chunk id = tid + NT*i -> (row, col)
+    u32x4 kst[C::KCH], vst[C::KCH];
+    uint32_t g_off = (uint32_t)(tid / C::CPR) * tok_bytes + 16 * (tid % C::CPR);   // chunk 0 of tile 0
+    const int lds_k_off = (tid / C::CPR) * C::KROW + 16 * (tid % C::CPR);
+    const int lds_v_off = (tid / C::CPR) * C::VROW + 16 * (tid % C::CPR);
 
-    // transposing-read role of this lane: row offset and byte offset inside a 32-column block
-    const int tr_row = ((lane & 15) >> 2) + 4 * hh;
-    const int tr_col = 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
-
-    auto load_tile = [&](int kv0) {
+    auto load_tile = [&]() {       // loads the tile at g_off and advances g_off by one tile
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
-            const int id = tid + NT * i;
-            const int row = id / C::CPR, col = id % C::CPR;
-            u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-            if (kv0 + row < Lkv) {
-                x = *(const u32x4 *)(kg + (size_t)(kv0 + row) * tok_stride + 8 * col);
-                y = *(const u32x4 *)(vg + (size_t)(kv0 + row) * tok_stride + 8 * col);
-            }
-            kreg[i] = x;
-            vreg[i] = y;
+            const uint32_t off = g_off + (uint32_t)i * C::ROWS_PER_PASS * tok_bytes;
+            kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
+            vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
         }
+        g_off += BN * tok_bytes;
     };
-
     auto store_tile = [&](int stage) {
         unsigned char *smK = smem + stage * C::STAGE;
         unsigned char *smV = smK + C::K_BYTES;
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
-            const int id = tid + NT * i;
-            const int row = id / C::CPR, col = id % C::CPR;
-            *(u32x4 *)(smK + row * C::KROW + 16 * col) = kreg[i];
-            *(u32x4 *)(smV + row * C::VROW + 16 * col) = vreg[i];
+            *(u32x4 *)(smK + lds_k_off + i * C::ROWS_PER_PASS * C::KROW) = kst[i];
+            *(u32x4 *)(smV + lds_v_off + i * C::ROWS_PER_PASS * C::VROW) = vst[i];
         }
     };
 
-    // ---- running softmax state and O^T accumulators
-    f32x16 o_acc[C::DB];
+    // lane roles inside a tile
+    const int k_frag_off = c * C::KROW + 16 * hh;                                   // + 32*KROW*kb + 32*t
+    const int v_frag_off = C::K_BYTES + (((lane & 15) >> 2) + 4 * hh) * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+
+    // ---- running softmax state and accumulators
+    f32x16 o_acc[C::DB];         // O^T blocks
+    f32x16 s_acc[2];             // S^T blocks of the tile in flight
+    bf16x8 pf[4];                // P^T fragments (B operands of the second GEMM)
+    bf16x8 fr[RING];             // A-operand fragments in flight from LDS
+    float m_run = -INFINITY;     // running max of scaled logits (log2 domain)
+    float l_run = 0.f;           // this lane's share of the running sum
 #pragma unroll
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
-    float m_run = -INFINITY;   // running max of scaled logits (log2 domain)
-    float l_run = 0.f;         // this lane's share of the running sum
 
-    const int ntiles = (Lkv + BN - 1) / BN;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int it = 0; it < ntiles; ++it) {
-        const int kv0 = it * BN;
-        const unsigned char *smK = smem + (it & 1) * C::STAGE;
-        const unsigned char *smV = smK + C::K_BYTES;
-        if (it + 1 < ntiles) load_tile(kv0 + BN);   // lands in registers while this tile is computed
-
-        // S^T = K Q^T for two 32-key blocks
-        f32x16 s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-            for (int t = 0; t < C::KS; ++t) {
-                const bf16x8 ka = *(const bf16x8 *)(smK + (32 * kb + c) * C::KROW + 32 * t + 16 * hh);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t], s[kb], 0, 0, 0);
+    // S^T = K Q^T against the K tile in `stage`: MFMA n uses k-step n/2 of key block n%2
+    auto chain_s = [&](int stage) {
+        const unsigned char *smK = smem + stage * C::STAGE + k_frag_off;
+        auto frag = [&](auto n_) -> bf16x8 {
+            constexpr int n = decltype(n_)::value;
+            return *(const bf16x8 *)(smK + 32 * (n & 1) * C::KROW + 32 * (n >> 1));
+        };
+        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = frag(m_); });
+        static_for<0, C::S_LEN>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+            constexpr int t = n >> 1, kb = n & 1;
+            if constexpr (n + PF < C::S_LEN) fr[(n + PF) % RING] = frag(std::integral_constant<int, n + PF>{});
+            if constexpr (t == 0) {
+                const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], zero, 0, 0, 0);
+            } else {
+                s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], s_acc[kb], 0, 0, 0);
             }
-        }
-        // keys past the end of the sequence (last tile only)
-        if (kv0 + BN > Lkv) {
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // O^T += V^T P^T with the V tile in `stage`: MFMA n uses 16-key step n/DB for row block n%DB
+    auto chain_pv = [&](int stage) {
+        const unsigned char *smV = smem + stage * C::STAGE + v_frag_off;
+        auto frag = [&](auto n_) -> bf16x8 {
+            constexpr int n = decltype(n_)::value;
+            const unsigned char *vp = smV + 16 * (n / C::DB) * C::VROW + 64 * (n % C::DB);
+            const bf16x4 lo = lds_read_tr(vp);                    // keys 16t + 4hh + 0..3
+            const bf16x4 hi = lds_read_tr(vp + 8 * C::VROW);      // keys 16t + 8 + 4hh + 0..3
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = frag(m_); });
+        static_for<0, C::PV_LEN>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+            constexpr int t = n / C::DB, db = n % C::DB;
+            if constexpr (n + PF < C::PV_LEN) fr[(n + PF) % RING] = frag(std::integral_constant<int, n + PF>{});
+            o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], pf[t], o_acc[db], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // Online softmax of the 32 logits per lane in s_acc -> P^T fragments in pf
+    auto softmax = [&](int kv0, auto masked_) {
+        constexpr bool masked = decltype(masked_)::value;
+        if constexpr (masked) {          // keys past the end of the sequence (last tile only)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int kvl = 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (kv0 + kvl >= Lkv) s[kb][r] = -INFINITY;
+                    if (kv0 + kvl >= Lkv) s_acc[kb][r] = -INFINITY;
                 }
         }
-        // online softmax for this lane's query column
-        float mx = s[0][0];
+        float mx = s_acc[0][0];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
         mx = xhalf_max(mx) * scale_log2;
         if (__any(mx > m_run + kRescaleThreshold)) {      // wave-uniform: rare after the first tiles
             const float m_new = fmaxf(m_run, mx);
@@ -196,47 +253,84 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
         }
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -m_run));
-                s[kb][r] = pv;
-                psum += pv;
-            }
-        l_run += psum;
-
-        // P^T fragments: accumulator registers 8*(t&1)..+7 of block t/2 are one B operand
-        bf16x8 pf[4];
+        const float mneg = -m_run;
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+        // accumulator registers 8*(t&1)..+7 of key block t/2 are one B operand
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) pf[t][j] = to_bf16(s[t >> 1][8 * (t & 1) + j]);
-
-        // O^T += V^T P^T
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const unsigned char *vp = smV + (16 * t + tr_row) * C::VROW + 64 * db + tr_col;
-                const bf16x4 lo = lds_read_tr(vp);                    // keys 16t + 4hh + 0..3
-                const bf16x4 hi = lds_read_tr(vp + 8 * C::VROW);      // keys 16t + 8 + 4hh + 0..3
-                const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[t], o_acc[db], 0, 0, 0);
+            for (int j = 0; j < 8; j += 2) {
+                const int r = 8 * (t & 1) + j;
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r], scale_log2, mneg));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r + 1], scale_log2, mneg));
+                bf16x2 pk;
+                pk[0] = to_bf16(p0);
+                pk[1] = to_bf16(p1);
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
+                pf[t][j] = pk[0];
+                pf[t][j + 1] = pk[1];
             }
-        }
-        if (it + 1 < ntiles) store_tile((it + 1) & 1);   // the other buffer was last read one tile ago
+    };
+
+    const int ntiles = (Lkv + BN - 1) / BN;
+    const std::false_type unmasked{};
+    const std::true_type masked{};
+
+    // ---- prologue: tiles 0 and 1 into the ring
+    load_tile();
+    store_tile(0);
+    load_tile();
+    store_tile(1);
+    __syncthreads();
+
+    // Barrier interval i (tile i in ring stage i % 3): tile i+2 is fetched into registers at its
+    // start and written to the stage of tile i-1 at its end (free since the barrier that opened
+    // the interval); the barrier that closes it publishes tile i+2 and retires tile i.
+    int st_cur = 0, st_next = 1, st_free = 2;
+    auto close_interval = [&]() {
+        store_tile(st_free);
         __syncthreads();
+        const int tmp = st_cur; st_cur = st_next; st_next = st_free; st_free = tmp;
+    };
+
+    if (group == 0) {
+#pragma unroll 1
+        for (int it = 0; it < ntiles - 1; ++it) {
+            load_tile();
+            chain_s(st_cur);
+            softmax(0, unmasked);
+            chain_pv(st_cur);
+            close_interval();
+        }
+        load_tile();
+        chain_s(st_cur);
+        softmax((ntiles - 1) * BN, masked);
+        chain_pv(st_cur);
+        close_interval();
+    } else {
+        chain_s(st_cur);
+#pragma unroll 1
+        for (int it = 0; it < ntiles - 1; ++it) {
+            load_tile();
+            softmax(0, unmasked);
+            chain_pv(st_cur);
+            chain_s(st_next);
+            close_interval();
+        }
+        load_tile();
+        softmax((ntiles - 1) * BN, masked);
+        chain_pv(st_cur);
+        close_interval();
     }
 
     // ---- epilogue ------------------------------------------------------------------------
-    const float l_tot = xhalf_sum(l_run);
-    const float inv_l = 1.0f / l_tot;
+    {
+        const float inv_l = 1.0f / xhalf_sum(l_run);
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db)
+        for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[db][r] *= inv_l;
+            for (int r = 0; r < 16; ++r) o_acc[db][r] *= inv_l;
+    }
 
     if (a.S != nullptr) {
         // O_inter^T[e][q] = sum_d S[d][e] * q[q][d], state as bf16 hi + lo, fp32 accumulate
@@ -315,10 +409,10 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     __syncthreads();
     bf16_t *og = (bf16_t *)a.out;
 #pragma unroll
-    for (int i = 0; i < 32 * C::CPR / 64; ++i) {
+    for (int i = 0; i < C::CPR / 2; ++i) {
         const int idx = lane + 64 * i;
         const int row = idx / C::CPR, col = idx % C::CPR;
-        const int orow = q0 + wave * 32 + row;
+        const int orow = q0 + row;
         if (orow < Lq) {
             const u32x4 x = *(const u32x4 *)(region + row * C::KROW + 16 * col);
             *(u32x4 *)(og + ((size_t)(b * (size_t)Lq + orow) * H + h) * D + 8 * col) = x;
@@ -333,6 +427,8 @@ hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream)
     const int n_qtiles = (a.Lq + BM - 1) / BM;
     const long long nwg = (long long)n_qtiles * a.B * a.H;
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
+    // the kernel addresses one stream's K (or V) with 32-bit byte offsets
+    if ((long long)(a.Lkv + 4 * BN) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     const float scale_log2 = a.sm_scale * 1.4426950408889634f;
     const dim3 grid((unsigned)nwg), block(NT);
     if (a.D == 128)
