@@ -99,6 +99,8 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+enum ChainKind { kNone = 0, kS = 1, kPV = 2 };
+
 template <int D>
 __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2)
 {
@@ -185,43 +187,45 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
 
-    // S^T = K Q^T against the K tile in `stage`: MFMA n uses k-step n/2 of key block n%2
-    auto chain_s = [&](int stage) {
-        const unsigned char *smK = smem + stage * C::STAGE + k_frag_off;
-        auto frag = [&](auto n_) -> bf16x8 {
-            constexpr int n = decltype(n_)::value;
-            return *(const bf16x8 *)(smK + 32 * (n & 1) * C::KROW + 32 * (n >> 1));
-        };
-        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = frag(m_); });
-        static_for<0, C::S_LEN>([&](auto n_) {
-            constexpr int n = decltype(n_)::value;
-            constexpr int t = n >> 1, kb = n & 1;
-            if constexpr (n + PF < C::S_LEN) fr[(n + PF) % RING] = frag(std::integral_constant<int, n + PF>{});
-            if constexpr (t == 0) {
-                const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], zero, 0, 0, 0);
-            } else {
-                s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], s_acc[kb], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-    // O^T += V^T P^T with the V tile in `stage`: MFMA n uses 16-key step n/DB for row block n%DB
-    auto chain_pv = [&](int stage) {
-        const unsigned char *smV = smem + stage * C::STAGE + v_frag_off;
-        auto frag = [&](auto n_) -> bf16x8 {
-            constexpr int n = decltype(n_)::value;
-            const unsigned char *vp = smV + 16 * (n / C::DB) * C::VROW + 64 * (n % C::DB);
+    // A-operand fragment n of a chain: for S^T = K Q^T (k-step n/2 of key block n%2) a K row
+    // piece, for O^T += V^T P^T (16-key step n/DB, row block n%DB) a transposed V piece.
+    auto load_frag = [&](auto kind_, int stage, auto n_) -> bf16x8 {
+        constexpr int n = decltype(n_)::value;
+        if constexpr (decltype(kind_)::value == kS) {
+            return *(const bf16x8 *)(smem + stage * C::STAGE + k_frag_off + 32 * (n & 1) * C::KROW + 32 * (n >> 1));
+        } else {
+            const unsigned char *vp = smem + stage * C::STAGE + v_frag_off + 16 * (n / C::DB) * C::VROW + 64 * (n % C::DB);
             const bf16x4 lo = lds_read_tr(vp);                    // keys 16t + 4hh + 0..3
             const bf16x4 hi = lds_read_tr(vp + 8 * C::VROW);      // keys 16t + 8 + 4hh + 0..3
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = frag(m_); });
-        static_for<0, C::PV_LEN>([&](auto n_) {
+        }
+    };
+    // Requests the first PF fragments of a chain (they must be in flight when the chain starts).
+    auto prefetch_chain = [&](auto kind_, int stage) {
+        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = load_frag(kind_, stage, m_); });
+    };
+    // Runs one MFMA chain; every step also requests the fragment needed PF MFMAs later, which at the
+    // end of the chain is a fragment of the chain that runs next (kind kNone: nothing follows).
+    auto run_chain = [&](auto kind_, int stage, auto next_kind_, int next_stage) {
+        constexpr int KIND = decltype(kind_)::value, NEXT = decltype(next_kind_)::value;
+        constexpr int LEN = KIND == kS ? C::S_LEN : C::PV_LEN;
+        static_for<0, LEN>([&](auto n_) {
             constexpr int n = decltype(n_)::value;
-            constexpr int t = n / C::DB, db = n % C::DB;
-            if constexpr (n + PF < C::PV_LEN) fr[(n + PF) % RING] = frag(std::integral_constant<int, n + PF>{});
-            o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], pf[t], o_acc[db], 0, 0, 0);
+            constexpr int m = n + PF;
+            if constexpr (m < LEN) fr[m % RING] = load_frag(kind_, stage, std::integral_constant<int, m>{});
+            else if constexpr (NEXT != kNone) fr[m % RING] = load_frag(next_kind_, next_stage, std::integral_constant<int, m - LEN>{});
+            if constexpr (KIND == kS) {
+                constexpr int t = n >> 1, kb = n & 1;
+                if constexpr (t == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], zero, 0, 0, 0);
+                } else {
+                    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], s_acc[kb], 0, 0, 0);
+                }
+            } else {
+                constexpr int t = n / C::DB, db = n % C::DB;
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], pf[t], o_acc[db], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -293,33 +297,37 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         const int tmp = st_cur; st_cur = st_next; st_next = st_free; st_free = tmp;
     };
 
+    const std::integral_constant<int, kS> S_{};
+    const std::integral_constant<int, kPV> PV_{};
+    const std::integral_constant<int, kNone> NONE_{};
+    prefetch_chain(S_, st_cur);
     if (group == 0) {
 #pragma unroll 1
         for (int it = 0; it < ntiles - 1; ++it) {
             load_tile();
-            chain_s(st_cur);
+            run_chain(S_, st_cur, PV_, st_cur);
             softmax(0, unmasked);
-            chain_pv(st_cur);
+            run_chain(PV_, st_cur, S_, st_next);
             close_interval();
         }
         load_tile();
-        chain_s(st_cur);
+        run_chain(S_, st_cur, PV_, st_cur);
         softmax((ntiles - 1) * BN, masked);
-        chain_pv(st_cur);
+        run_chain(PV_, st_cur, NONE_, 0);
         close_interval();
     } else {
-        chain_s(st_cur);
+        run_chain(S_, st_cur, PV_, st_cur);
 #pragma unroll 1
         for (int it = 0; it < ntiles - 1; ++it) {
             load_tile();
             softmax(0, unmasked);
-            chain_pv(st_cur);
-            chain_s(st_next);
+            run_chain(PV_, st_cur, S_, st_next);
+            run_chain(S_, st_next, PV_, st_next);
             close_interval();
         }
         load_tile();
         softmax((ntiles - 1) * BN, masked);
-        chain_pv(st_cur);
+        run_chain(PV_, st_cur, NONE_, 0);
         close_interval();
     }
 
