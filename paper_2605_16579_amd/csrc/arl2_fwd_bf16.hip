@@ -15,22 +15,18 @@
 // V^T fragments come from the row-major V tile in LDS through the transposing LDS read
 // (ds_read_b64_tr_b16), four keys per read.
 //
-// A wavefront cannot overlap its own VALU work with its own MFMAs on this hardware, but the
-// two wavefronts that share a SIMD can overlap each other.  The wavefronts of a workgroup
-// therefore run the same per-tile work in two rotations, half a tile apart:
-//
-//   wavefronts 0-3:   S(i)        softmax(i)   PV(i)      | barrier
-//   wavefronts 4-7:   softmax(i)  PV(i)        S(i+1)     | barrier
-//
-// so the softmax arithmetic of one group is issued while the other group keeps the matrix
-// cores busy.  Inside an MFMA chain every step issues one MFMA and the LDS read of the operand
-// fragment needed several MFMAs later.
+// Per key tile every wavefront runs S = K Q^T (16 MFMAs), the online softmax of its 32 logits
+// per lane (VALU), then O += V^T P^T (16 MFMAs).  On this hardware a wavefront does not overlap
+// its own VALU work with its own MFMAs; the overlap comes from the second wavefront on the
+// same SIMD, which the MFMA arbitration keeps about one phase behind the first.  Inside an MFMA
+// chain every step issues one MFMA and the LDS read of the operand fragment needed seven MFMAs
+// later, across chain boundaries, so the matrix pipe never waits for LDS latency.
 //
 // K/V tiles travel HBM/L2 -> registers (buffer loads, zero beyond the last key) -> a 3-stage
 // LDS ring with one workgroup barrier per tile.  The running maximum is only raised when a
 // row's tile maximum exceeds it by more than 2^8, which removes the accumulator rescale from
-// almost every tile without changing the normalised result.  Row sums are taken over the
-// bf16-rounded probabilities that the second GEMM actually multiplies.
+// almost every tile without changing the normalised result.  (Row sums use plain fp32 adds:
+// the bf16 dot-product instruction measured far slower next to MFMAs.)
 //
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
 // state split into bf16 hi + lo parts staged through the (now free) LDS, the raw bf16 q
@@ -109,7 +105,6 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, c = lane & 31, hh = lane >> 5;
-    const int group = wave >> 2;      // 0: S, softmax, PV per barrier interval; 1: softmax, PV, next S
 
     const int work = xcd_contiguous_id(blockIdx.x, gridDim.x);
     const int qt = work % n_qtiles;
@@ -258,7 +253,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
         }
         const float mneg = -m_run;
-        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+        float psum = 0.f;
         // accumulator registers 8*(t&1)..+7 of key block t/2 are one B operand
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -270,10 +265,11 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
                 bf16x2 pk;
                 pk[0] = to_bf16(p0);
                 pk[1] = to_bf16(p1);
-                l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
+                psum += p0 + p1;
                 pf[t][j] = pk[0];
                 pf[t][j + 1] = pk[1];
             }
+        l_run += psum;
     };
 
     const int ntiles = (Lkv + BN - 1) / BN;
@@ -301,35 +297,19 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     const std::integral_constant<int, kPV> PV_{};
     const std::integral_constant<int, kNone> NONE_{};
     prefetch_chain(S_, st_cur);
-    if (group == 0) {
 #pragma unroll 1
-        for (int it = 0; it < ntiles - 1; ++it) {
-            load_tile();
-            run_chain(S_, st_cur, PV_, st_cur);
-            softmax(0, unmasked);
-            run_chain(PV_, st_cur, S_, st_next);
-            close_interval();
-        }
+    for (int it = 0; it < ntiles - 1; ++it) {
         load_tile();
         run_chain(S_, st_cur, PV_, st_cur);
-        softmax((ntiles - 1) * BN, masked);
-        run_chain(PV_, st_cur, NONE_, 0);
-        close_interval();
-    } else {
-        run_chain(S_, st_cur, PV_, st_cur);
-#pragma unroll 1
-        for (int it = 0; it < ntiles - 1; ++it) {
-            load_tile();
-            softmax(0, unmasked);
-            run_chain(PV_, st_cur, S_, st_next);
-            run_chain(S_, st_next, PV_, st_next);
-            close_interval();
-        }
-        load_tile();
-        softmax((ntiles - 1) * BN, masked);
-        run_chain(PV_, st_cur, NONE_, 0);
+        softmax(0, unmasked);
+        run_chain(PV_, st_cur, S_, st_next);
         close_interval();
     }
+    load_tile();
+    run_chain(S_, st_cur, PV_, st_cur);
+    softmax((ntiles - 1) * BN, masked);
+    run_chain(PV_, st_cur, NONE_, 0);
+    __syncthreads();
 
     // ---- epilogue ------------------------------------------------------------------------
     {
