@@ -42,34 +42,29 @@ def commit_bytes(B, H, L, D, io_bytes):
     return B * (2.0 * L * H * D * io_bytes + 2.0 * H * D * D * 4.0)
 
 
-def cpu_baseline(w, passes_inputs, clean, S0, rows_per_head):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample: `rows_per_head`
-    query rows of one readout pass (every row costs the same) and one full commit; the chunk step
-    time is extrapolated as passes * (row time * L / rows) + commit time."""
+def cpu_baseline(w, passes_inputs, clean, S0, steps):
+    """The oracle as it stands (fp64, OpenMP over independent rows), timed on this machine's host cores
+    on whole chunk steps of the same workload: every readout pass in full, then the commit."""
     import numpy as np
 
     import workloads as W
     from oracle import arl2_oracle as O
     O.build()
     f = W.as_f32_numpy
-    q, k, v, g = passes_inputs[0]
-    rows = np.linspace(0, w.L - 1, rows_per_head).astype(np.int32)
     S64 = S0.astype(np.float64)
-    qf, kf, vf, gf = f(q), f(k), f(v), f(g)
+    ins = [tuple(f(t) for t in pi) for pi in passes_inputs]
+    kc, vc, gate = (f(t) for t in clean)
+    O.fwd(ins[0][0][:, :8], ins[0][1], ins[0][2], S64, ins[0][3][:, :8])     # warm-up: load the library, spin up threads
     t0 = time.perf_counter()
-    O.fwd(qf, kf, vf, S64, gf, rows=rows)
-    t_rows = time.perf_counter() - t0
-    kc, vc, gate = clean
-    kcf, vcf, gatef = f(kc), f(vc), f(gate)
-    t0 = time.perf_counter()
-    O.commit(kcf, vcf, gatef, S64)
-    t_commit = time.perf_counter() - t0
-    t_step = w.passes * t_rows * (w.L / len(rows)) + t_commit
+    for _ in range(steps):
+        for (q, k, v, g) in ins:
+            O.fwd(q, k, v, S64, g)
+        S64 = O.commit(kc, vc, gate, S64)
+    t_step = (time.perf_counter() - t0) / steps
     return {
         "value": w.B * w.L / t_step, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
-        "sample": f"fp64 oracle: {len(rows)} of {w.L} query rows per head of one readout pass "
-                  f"({t_rows:.2f} s) + one full commit ({t_commit:.2f} s); step time extrapolated to "
-                  f"{w.passes} passes + 1 commit = {t_step:.1f} s",
+        "sample": f"fp64 oracle, {steps} whole chunk step(s) of {w.name} ({w.passes} full readout passes + 1 commit), "
+                  f"{t_step:.2f} s per step",
     }
 
 
@@ -79,8 +74,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="query rows per head timed on the CPU oracle")
+    ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of 256 MiB (5 times): the reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (heads and streams are independent, so the step "
@@ -98,6 +96,15 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "copies": 5}))
+        return 0
     w = W.WORKLOADS[args.workload]
     io_bytes = 2 if w.io_dtype == "bf16" else 4
 
@@ -181,7 +188,7 @@ def main() -> int:
         if t:
             result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_rows)
+        result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps)
     print(json.dumps(result), flush=True)
     return 0
 
