@@ -23,10 +23,13 @@
 // later, across chain boundaries, so the matrix pipe never waits for LDS latency.
 //
 // K/V tiles travel HBM/L2 -> registers (buffer loads, zero beyond the last key) -> a 3-stage
-// LDS ring with one workgroup barrier per tile.  The running maximum is only raised when a
-// row's tile maximum exceeds it by more than 2^8, which removes the accumulator rescale from
-// almost every tile without changing the normalised result.  (Row sums use plain fp32 adds:
-// the bf16 dot-product instruction measured far slower next to MFMAs.)
+// LDS ring with one workgroup barrier per tile.  The softmax is optimistic: probabilities are
+// taken relative to the running maximum as it stands, and only when a lane's share of the row
+// sum shows that a logit exceeded it by more than ~2^7 (or on the first tile) is the true tile
+// maximum computed, the running maximum raised, the accumulators rescaled and the tile redone.
+// This removes the per-tile maximum reduction and the accumulator rescale from the steady
+// state without changing the normalised result.  (Row sums use plain fp32 adds: the bf16
+// dot-product instruction measured far slower next to MFMAs.)
 //
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
 // state split into bf16 hi + lo parts staged through the (now free) LDS, the raw bf16 q
@@ -68,8 +71,9 @@ struct FwdCfg {
     static_assert(S_LEN % RING == 0 && PV_LEN % RING == 0, "chain lengths must be multiples of the fragment ring");
 };
 
-// Raise the running maximum only when the tile maximum exceeds it by more than this (log2 units).
-constexpr float kRescaleThreshold = 8.0f;
+// The running maximum is raised only when a lane's share of a tile's row sum (32 probabilities taken
+// relative to the running maximum) reaches this value, i.e. some logit exceeded it by more than ~2^7.
+constexpr float kRowSumLimit = 4096.0f;
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
@@ -224,7 +228,29 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    // Online softmax of the 32 logits per lane in s_acc -> P^T fragments in pf
+    // exp2 of all 32 logits per lane relative to the running maximum -> P^T fragments in pf;
+    // returns this lane's share of the row sum.  Accumulator registers 8*(t&1)..+7 of key block
+    // t/2 are one B operand (fragment t) of the second GEMM.
+    auto exp_all = [&]() -> float {
+        const float mneg = -m_run;
+        float psum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                const int r = 8 * (t & 1) + j;
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r], scale_log2, mneg));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r + 1], scale_log2, mneg));
+                psum += p0 + p1;
+                pf[t][j] = to_bf16(p0);
+                pf[t][j + 1] = to_bf16(p1);
+            }
+        return psum;
+    };
+    // Online softmax of the tile in s_acc.  The probabilities are first taken relative to the running
+    // maximum as it stands; only if some lane's share of the row sum shows that a logit exceeded it by
+    // more than the threshold (or the maximum is still -inf: first tile) is the true tile maximum
+    // computed, the running maximum raised, the accumulators rescaled and the tile redone.
     auto softmax = [&](int kv0, auto masked_) {
         constexpr bool masked = decltype(masked_)::value;
         if constexpr (masked) {          // keys past the end of the sequence (last tile only)
@@ -236,39 +262,24 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
                     if (kv0 + kvl >= Lkv) s_acc[kb][r] = -INFINITY;
                 }
         }
-        float mx = s_acc[0][0];
+        float psum = exp_all();
+        if (__any(!(psum < kRowSumLimit))) {      // wave-uniform and rare; also true for inf and NaN
+            float mx = s_acc[0][0];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
-        mx = xhalf_max(mx) * scale_log2;
-        if (__any(mx > m_run + kRescaleThreshold)) {      // wave-uniform: rare after the first tiles
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
+            mx = xhalf_max(mx) * scale_log2;
             const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < C::DB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+            psum = exp_all();
         }
-        const float mneg = -m_run;
-        float psum = 0.f;
-        // accumulator registers 8*(t&1)..+7 of key block t/2 are one B operand
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int j = 0; j < 8; j += 2) {
-                const int r = 8 * (t & 1) + j;
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r], scale_log2, mneg));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r + 1], scale_log2, mneg));
-                bf16x2 pk;
-                pk[0] = to_bf16(p0);
-                pk[1] = to_bf16(p1);
-                psum += p0 + p1;
-                pf[t][j] = pk[0];
-                pf[t][j + 1] = pk[1];
-            }
         l_run += psum;
     };
 
