@@ -1,14 +1,19 @@
 // Post-denoise state commit on bf16 MFMA (gfx950):
 //   S <- gate * S + sum_i k'_i^T v_i,   k'_i = k_i / sqrt(|k_i|^2 + eps)     paper Eq. (3), Eq. (4)
 //
-// The contraction runs over tokens, so both operands are needed token-major per feature:
-// every workgroup transposes 64-token tiles of K and V through LDS.  To keep the fp32 state
-// accurate the raw bf16 K (exact) is one operand and the row-scaled values r_i * v_i, split
-// into bf16 hi + lo parts, are the other (two MFMAs per tile step, error ~2^-17).
+// HBM-bound: every k and v element is read once.  The contraction runs over tokens, so both MFMA
+// operands are needed token-major per feature; 64-token tiles of K and V are written to LDS row-major
+// (as they arrive, 16-byte pieces) and read back through the transposing LDS read
+// (ds_read_b64_tr_b16), which hands every lane four tokens of one feature.  To keep the fp32 state
+// accurate the raw bf16 K (exact) is one operand and the row-scaled values r_i * v_i, split into
+// bf16 hi + lo parts, are the other (two MFMAs per step, error ~2^-17; one bf16 rounding of the
+// scaled values would cost ~1e-3 on the state).  The scale r_i = 1/sqrt(|k_i|^2 + eps) is computed
+// from the K registers on their way to LDS (lane shuffles across the 16 lanes that share a row).
 //
-// Tokens are split over `nsplit` workgroups per (stream, head); each writes a D x D fp32
-// partial to the workspace.  A second kernel adds the partials in split order and applies the
-// gate to the old state, so the result is bit-identical from run to run.
+// Tokens are split over `nsplit` workgroups per (stream, head); each keeps the next tile's loads in
+// flight while it works on the current one and finally writes a D x D fp32 partial to the workspace.
+// A second kernel adds the partials in split order and applies the gate to the old state, so the
+// result is bit-identical from run to run (no floating-point atomics).
 #include "arl2_device.h"
 
 namespace arl2 {
@@ -17,158 +22,187 @@ namespace {
 constexpr int BT = 64;    // tokens per tile
 constexpr int NT = 256;
 
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char *p, int second_row_bytes)
+{
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p + second_row_bytes));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
 template <int D>
 struct CommitCfg {
-    static constexpr int DB = D / 32;
-    static constexpr int CPR = D / 8;
-    static constexpr int ROW = 2 * BT + 8;              // LDS bytes per transposed row (64 tokens + pad)
-    static constexpr int MAT = D * ROW;                 // one transposed D x 64 matrix
-    static constexpr int NEB = DB * DB / 4;             // e-blocks per wave
+    static constexpr int CPR = D / 8;                   // 16-byte chunks per row
+    static constexpr int ROW = 2 * D + 64;              // LDS bytes per tile row (conflict-free transposing reads)
+    static constexpr int MAT = BT * ROW;                // one 64-token tile
+    static constexpr int STAGE = 3 * MAT;               // K, V' hi, V' lo
+    static constexpr int KCH = BT * CPR / NT;           // chunks per thread per tile (K and V each)
+    static constexpr int ROWS_PER_PASS = NT / CPR;
+    static constexpr int HB = D / 64;                   // 64-wide halves per dimension
+    static constexpr int WAVES_USED = HB * HB;          // wavefronts that own a 64 x 64 output quadrant
 };
 
 template <int D>
 __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
 {
     using C = CommitCfg<D>;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[3 * C::MAT];
-    unsigned char *smKt = smem, *smVh = smem + C::MAT, *smVl = smem + 2 * C::MAT;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE];
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, c = lane & 31, hh = lane >> 5;
+    const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
     const int split = blockIdx.x % a.nsplit;
     const int bh = blockIdx.x / a.nsplit;
     const int h = bh % a.H, b = bh / a.H;
     const int L = a.L, H = a.H;
-    const size_t tok_stride = (size_t)H * D;
+    const uint32_t tok_bytes = (uint32_t)H * D * 2;
     const bf16_t *kg = (const bf16_t *)a.k + ((size_t)b * L * H + h) * D;
     const bf16_t *vg = (const bf16_t *)a.v + ((size_t)b * L * H + h) * D;
+    const uint32_t range = (uint32_t)(L - 1) * tok_bytes + 2 * D;      // bytes of this head's slice
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(kg, range);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(vg, range);
 
     const int ntiles = (L + BT - 1) / BT;
     const int t_begin = (int)((long long)split * ntiles / a.nsplit);
     const int t_end = (int)((long long)(split + 1) * ntiles / a.nsplit);
 
-    const int dg = tid % C::CPR, u = tid / C::CPR;      // 8-feature group, 4-token group
-    const bool active = u < BT / 4;
-
-    const int dblk = wave % C::DB;
-    const int eb0 = (wave / C::DB) * C::NEB;
-    f32x16 acc[C::NEB];
+    // chunk i of this thread: row (tid / CPR) + ROWS_PER_PASS * i, 16-byte column tid % CPR
+    uint32_t g_off = ((uint32_t)t_begin * BT + tid / C::CPR) * tok_bytes + 16 * (tid % C::CPR);
+    const int lds_off = (tid / C::CPR) * C::ROW + 16 * (tid % C::CPR);
+    u32x4 kr[C::KCH], vr[C::KCH];
+    auto load_tile = [&]() {        // rows past the end of the sequence read as zero
 #pragma unroll
-    for (int n = 0; n < C::NEB; ++n)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
-
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        const int tok0 = tile * BT;
-        u32x4 kr[4], vr[4];
-        if (active) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int tok = tok0 + 4 * u + e;
-                u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-                if (tok < L) {
-                    x = *(const u32x4 *)(kg + (size_t)tok * tok_stride + 8 * dg);
-                    y = *(const u32x4 *)(vg + (size_t)tok * tok_stride + 8 * dg);
-                }
-                kr[e] = x;
-                vr[e] = y;
-            }
+        for (int i = 0; i < C::KCH; ++i) {
+            const uint32_t off = g_off + (uint32_t)i * C::ROWS_PER_PASS * tok_bytes;
+            kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
+            vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
         }
-        // 1 / sqrt(|k_tok|^2 + eps): partial sums over this thread's 8 features, then over the
-        // CPR consecutive lanes that share the token rows
-        float rn[4];
+        g_off += BT * tok_bytes;
+    };
+    // K as it is, and r * V split into bf16 hi + lo, into the LDS stage
+    auto stage_tile = [&](int stage) {
+        unsigned char *sm = smem + stage * C::STAGE + lds_off;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int i = 0; i < C::KCH; ++i) {
             float ss = 0.f;
-            if (active) {
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float lo = __uint_as_float(kr[e][w] << 16);
-                    const float hi = __uint_as_float(kr[e][w] & 0xffff0000u);
-                    ss = fmaf(lo, lo, ss);
-                    ss = fmaf(hi, hi, ss);
-                }
+            for (int w = 0; w < 4; ++w) {
+                const float lo = __uint_as_float(kr[i][w] << 16);
+                const float hi = __uint_as_float(kr[i][w] & 0xffff0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
             }
 #pragma unroll
             for (int off = 1; off < C::CPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
-            rn[e] = 1.0f / sqrtf(ss + a.l2_eps);
-        }
-
-        __syncthreads();            // previous tile fully consumed
-        if (active) {
+            const float rn = 1.0f / sqrtf(ss + a.l2_eps);
+            union { u32x4 u; bf16x8 v; } vh, vl;
 #pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                const int w = m >> 1;
-                const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
-                u32x2 o;
-                o[0] = __builtin_amdgcn_perm(kr[1][w], kr[0][w], sel);
-                o[1] = __builtin_amdgcn_perm(kr[3][w], kr[2][w], sel);
-                *(u32x2 *)(smKt + (8 * dg + m) * C::ROW + 8 * u) = o;
-                bf16x4 vh, vl;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t word = vr[e][w];
-                    const float val = (m & 1) ? __uint_as_float(word & 0xffff0000u) : __uint_as_float(word << 16);
-                    const float sv = val * rn[e];
-                    const bf16_t hi = to_bf16(sv);
-                    vh[e] = hi;
-                    vl[e] = to_bf16(sv - (float)hi);
-                }
-                *(bf16x4 *)(smVh + (8 * dg + m) * C::ROW + 8 * u) = vh;
-                *(bf16x4 *)(smVl + (8 * dg + m) * C::ROW + 8 * u) = vl;
+            for (int w = 0; w < 4; ++w) {
+                const float s0 = __uint_as_float(vr[i][w] << 16) * rn;
+                const float s1 = __uint_as_float(vr[i][w] & 0xffff0000u) * rn;
+                const bf16_t h0 = to_bf16(s0), h1 = to_bf16(s1);
+                vh.v[2 * w] = h0;
+                vh.v[2 * w + 1] = h1;
+                vl.v[2 * w] = to_bf16(s0 - (float)h0);
+                vl.v[2 * w + 1] = to_bf16(s1 - (float)h1);
             }
+            unsigned char *p = sm + i * C::ROWS_PER_PASS * C::ROW;
+            *(u32x4 *)(p) = kr[i];
+            *(u32x4 *)(p + C::MAT) = vh.u;
+            *(u32x4 *)(p + 2 * C::MAT) = vl.u;
         }
-        __syncthreads();
+    };
 
+    // this wavefront's 64 x 64 quadrant of the D x D partial: feature blocks d0, d0+1 x e0, e0+1
+    const bool compute = wave < C::WAVES_USED;
+    const int d0 = 2 * (wave / C::HB), e0 = 2 * (wave % C::HB);
+    const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    f32x16 acc[2][2];
 #pragma unroll
-        for (int t = 0; t < BT / 16; ++t) {
-            const int off = 32 * t + 16 * hh;
-            union { u32x2 u2[2]; bf16x8 v; } ka;
-            const unsigned char *kp = smKt + (32 * dblk + c) * C::ROW + off;
-            ka.u2[0] = *(const u32x2 *)kp;
-            ka.u2[1] = *(const u32x2 *)(kp + 8);
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int n = 0; n < C::NEB; ++n) {
-                union { u32x2 u2[2]; bf16x8 v; } bh_, bl_;
-                const unsigned char *hp = smVh + (32 * (eb0 + n) + c) * C::ROW + off;
-                const unsigned char *lp = smVl + (32 * (eb0 + n) + c) * C::ROW + off;
-                bh_.u2[0] = *(const u32x2 *)hp;
-                bh_.u2[1] = *(const u32x2 *)(hp + 8);
-                bl_.u2[0] = *(const u32x2 *)lp;
-                bl_.u2[1] = *(const u32x2 *)(lp + 8);
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, bh_.v, acc[n], 0, 0, 0);
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, bl_.v, acc[n], 0, 0, 0);
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    if (t_begin < t_end) load_tile();
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const int stage = (tile - t_begin) & 1;
+        stage_tile(stage);               // waits for this tile's loads
+        __syncthreads();                 // also: every wave is done with the MFMAs of the tile before last
+        if (tile + 1 < t_end) load_tile();
+        if (compute) {
+            const unsigned char *sm = smem + stage * C::STAGE + tr_off;
+#pragma unroll
+            for (int t = 0; t < BT / 16; ++t) {
+                const unsigned char *row = sm + 16 * t * C::ROW;     // tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
+                bf16x8 ka[2], vh[2], vl[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    ka[i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
+                    vh[i] = lds_read_tr_pair(row + C::MAT + 64 * (e0 + i), 8 * C::ROW);
+                    vl[i] = lds_read_tr_pair(row + 2 * C::MAT + 64 * (e0 + i), 8 * C::ROW);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], vh[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], vl[j], acc[i][j], 0, 0, 0);
+                    }
             }
         }
     }
 
     // partial[bh][split][d][e]
-    float *part = (float *)a.workspace + ((size_t)bh * a.nsplit + split) * D * D;
+    if (compute) {
+        float *part = (float *)a.workspace + ((size_t)bh * a.nsplit + split) * D * D;
 #pragma unroll
-    for (int n = 0; n < C::NEB; ++n)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int d = 32 * dblk + 8 * (r >> 2) + 4 * hh + (r & 3);
-            const int e = 32 * (eb0 + n) + c;
-            part[(size_t)d * D + e] = acc[n][r];
-        }
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int d = 32 * (d0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int e = 32 * (e0 + j) + (lane & 31);
+                    part[(size_t)d * D + e] = acc[i][j][r];
+                }
+    }
 }
 
 // S[bh] = gate[bh] * S[bh] + sum_{split ascending} partial[bh][split]
+template <int NS>
 __global__ __launch_bounds__(NT) void commit_reduce_kernel(CommitArgs a, int vec_per_head)
 {
     const int bh = blockIdx.x / (vec_per_head / NT);
     const int vi = (blockIdx.x % (vec_per_head / NT)) * NT + threadIdx.x;
     const size_t head_elems = (size_t)vec_per_head * 4;
-    const f32x4 *part = (const f32x4 *)((const float *)a.workspace + (size_t)bh * a.nsplit * head_elems);
-    f32x4 sum = part[vi];
-    for (int s = 1; s < a.nsplit; ++s) sum += part[(size_t)s * vec_per_head + vi];
-    const float gate = a.gate[bh];
+    const f32x4 *part = (const f32x4 *)((const float *)a.workspace + (size_t)bh * a.nsplit * head_elems) + vi;
     f32x4 *Sg = (f32x4 *)(a.S + (size_t)bh * head_elems);
+    const float gate = a.gate[bh];
     const f32x4 old = Sg[vi];
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    // all loads of a batch are issued before the adds; the adds run in split order
+    for (int s0 = 0; s0 < a.nsplit; s0 += NS) {
+        f32x4 x[NS];
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            x[j] = (s0 + j < a.nsplit) ? part[(size_t)(s0 + j) * vec_per_head] : zero;
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sum[c] += x[j][c];
+    }
     f32x4 res;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) res[j] = fmaf(gate, old[j], sum[j]);
+    for (int c = 0; c < 4; ++c) res[c] = fmaf(gate, old[c], sum[c]);
     Sg[vi] = res;
 }
 
@@ -177,8 +211,8 @@ __global__ __launch_bounds__(NT) void commit_reduce_kernel(CommitArgs a, int vec
 int commit_nsplit(int B, int H, int L)
 {
     const int ntiles = (L + BT - 1) / BT;
-    long long bh = (long long)B * H;
-    long long want = (256 + bh - 1) / bh;      // aim at about one workgroup per compute unit
+    const long long bh = (long long)B * H;
+    long long want = (192 + bh - 1) / bh;      // enough workgroups in flight to saturate HBM
     if (want < 1) want = 1;
     if (want > ntiles) want = ntiles;
     if (want > 32) want = 32;
@@ -189,6 +223,8 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
 {
     const long long nwg = (long long)a.B * a.H * a.nsplit;
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
+    // the kernel addresses one stream's K (or V) with 32-bit byte offsets
+    if ((long long)(a.L + 4 * BT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.D == 128)
         hipLaunchKernelGGL(commit_partial_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else if (a.D == 64)
@@ -199,7 +235,7 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
     if (e != hipSuccess) return e;
     const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
     const long long rwg = (long long)a.B * a.H * (vec_per_head / NT);
-    hipLaunchKernelGGL(commit_reduce_kernel, dim3((unsigned)rwg), dim3(NT), 0, stream, a, vec_per_head);
+    hipLaunchKernelGGL(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NT), 0, stream, a, vec_per_head);
     return hipGetLastError();
 }
 
