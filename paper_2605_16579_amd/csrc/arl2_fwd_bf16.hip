@@ -32,8 +32,9 @@
 // dot-product instruction measured far slower next to MFMAs.)
 //
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
-// state split into bf16 hi + lo parts staged through the (now free) LDS, the raw bf16 q
-// fragments as B operand, and the L2 norm of q applied as an fp32 per-column scale.
+// state split into bf16 hi + lo parts, staged row-major through the (now free) LDS and read
+// transposed like V, the raw bf16 q fragments as B operand, and the L2 norm of q applied as an
+// fp32 per-column scale.
 #include "arl2_device.h"
 
 #include <type_traits>
@@ -59,7 +60,9 @@ struct FwdCfg {
     static constexpr int V_BYTES = BN * VROW;
     static constexpr int STAGE = K_BYTES + V_BYTES;   // one K/V tile
     static constexpr int KV_BYTES = NSTAGE * STAGE;
-    static constexpr int ST_BYTES = D * KROW;    // state staging [e][d]
+    static constexpr int SS_BYTES = D * VROW;    // one bf16 part of the state staged [d][e]
+    static constexpr int ST_BYTES = 2 * SS_BYTES;
+    static constexpr int SCH = (D * CPR + NT - 1) / NT;   // 8-float state pieces per thread
     static constexpr int OUT_BYTES = BM * KROW;  // output staging [q][e]
     static constexpr int SMEM = (KV_BYTES > ST_BYTES ? (KV_BYTES > OUT_BYTES ? KV_BYTES : OUT_BYTES)
                                                      : (ST_BYTES > OUT_BYTES ? ST_BYTES : OUT_BYTES));
@@ -332,54 +335,51 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     }
 
     if (a.S != nullptr) {
-        // O_inter^T[e][q] = sum_d S[d][e] * q[q][d], state as bf16 hi + lo, fp32 accumulate
+        // O_inter^T[e][q] = sum_d S[d][e] * q[q][d]: the fp32 state is split into bf16 hi + lo parts
+        // (fp32 accumulate), both staged row-major [d][e] in LDS and read as S^T fragments through the
+        // transposing LDS read, exactly like V.
         const float *Sg = a.S + ((size_t)b * H + h) * D * D;
+        unsigned char *smHi = smem, *smLo = smem + C::SS_BYTES;
+        __syncthreads();                              // every wave is done with the K/V ring
+#pragma unroll
+        for (int i = 0; i < C::SCH; ++i) {
+            const int id = tid + NT * i;              // 8-float piece: row id / CPR, column piece id % CPR
+            if (id < D * C::CPR) {
+                const float *sp = Sg + (size_t)(id / C::CPR) * D + 8 * (id % C::CPR);
+                const f32x4 x0 = *(const f32x4 *)(sp);
+                const f32x4 x1 = *(const f32x4 *)(sp + 4);
+                union { u32x4 u; bf16x8 v; } hi, lo;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float x = j < 4 ? x0[j] : x1[j - 4];
+                    const bf16_t hb = to_bf16(x);
+                    hi.v[j] = hb;
+                    lo.v[j] = to_bf16(x - (float)hb);
+                }
+                const int off = (id / C::CPR) * C::VROW + 16 * (id % C::CPR);
+                *(u32x4 *)(smHi + off) = hi.u;
+                *(u32x4 *)(smLo + off) = lo.u;
+            }
+        }
+        __syncthreads();
         f32x16 inter[C::DB];
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) inter[db][r] = 0.f;
-
-        constexpr int NBLK = D * D / 32;              // 4(d) x 8(e) blocks of the state
-        constexpr int BPT = (NBLK + NT - 1) / NT;
-#pragma unroll 1
-        for (int part = 0; part < 2; ++part) {        // 0: hi part, 1: lo part
-            __syncthreads();                          // LDS free (main loop / previous part done)
+        // k-slot j of half-wave hh must be d = 16t + 8hh + j to match the q fragments
+        const int s_frag_off = (8 * hh + ((lane & 15) >> 2)) * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
 #pragma unroll
-            for (int i = 0; i < BPT; ++i) {
-                const int id = tid + NT * i;
-                if (id < NBLK) {
-                    const int eg = id % C::CPR, du = id / C::CPR;
-                    const float *sp = Sg + (size_t)(4 * du) * D + 8 * eg;
-                    float x[4][8];
+        for (int t = 0; t < C::KS; ++t)
 #pragma unroll
-                    for (int dd = 0; dd < 4; ++dd) {
-                        const f32x4 lo4 = *(const f32x4 *)(sp + dd * D);
-                        const f32x4 hi4 = *(const f32x4 *)(sp + dd * D + 4);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) { x[dd][j] = lo4[j]; x[dd][4 + j] = hi4[j]; }
-                    }
-#pragma unroll
-                    for (int m = 0; m < 8; ++m) {
-                        bf16x4 w;
-#pragma unroll
-                        for (int dd = 0; dd < 4; ++dd) {
-                            const bf16_t hi = to_bf16(x[dd][m]);
-                            w[dd] = part == 0 ? hi : to_bf16(x[dd][m] - (float)hi);
-                        }
-                        *(bf16x4 *)(smem + (8 * eg + m) * C::KROW + 8 * du) = w;
-                    }
-                }
+            for (int db = 0; db < C::DB; ++db) {
+                const unsigned char *p = smHi + s_frag_off + 16 * t * C::VROW + 64 * db;
+                const bf16x8 sh = __builtin_shufflevector(lds_read_tr(p), lds_read_tr(p + 4 * C::VROW), 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 sl = __builtin_shufflevector(lds_read_tr(p + C::SS_BYTES), lds_read_tr(p + C::SS_BYTES + 4 * C::VROW),
+                                                          0, 1, 2, 3, 4, 5, 6, 7);
+                inter[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sh, qf[t], inter[db], 0, 0, 0);
+                inter[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sl, qf[t], inter[db], 0, 0, 0);
             }
-            __syncthreads();
-#pragma unroll
-            for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                for (int t = 0; t < C::KS; ++t) {
-                    const bf16x8 sa = *(const bf16x8 *)(smem + (32 * db + c) * C::KROW + 32 * t + 16 * hh);
-                    inter[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qf[t], inter[db], 0, 0, 0);
-                }
-        }
         // gate * L2 norm scale for this lane's query row
         float gq = 1.0f / sqrtf(qss + a.l2_eps);
         if (a.g != nullptr && qrow < Lq) {
