@@ -71,8 +71,8 @@ def cpu_baseline(w, passes_inputs, clean, S0, steps):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
     ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -122,23 +122,20 @@ def main() -> int:
     torch.cuda.synchronize()
     S0 = S.detach().cpu().numpy().copy()
 
+    # Two events per step on the launch stream: before the first readout pass and after the last one
+    # (a record between every pair of launches costs ~15 % of the step on this machine).
     def step(events=None):
+        if events is not None:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e0.record()
         for p in range(w.passes):
             q, k, v, g = passes[p]
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
             A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
-            if events is not None:
-                e1.record()
-                events.append((e0, e1))
         if events is not None:
-            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            c0.record()
+            e1 = torch.cuda.Event(enable_timing=True)
+            e1.record()
+            events.append((e0, e1))
         A.arl2_state_commit(kc, vc, gate, S, ws)
-        if events is not None:
-            c1.record()
-            events.append((c0, c1))
 
     for _ in range(args.warmup):
         step()
@@ -147,13 +144,17 @@ def main() -> int:
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(events)
+    end = torch.cuda.Event(enable_timing=True)
+    end.record()
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
 
     ms_per_step = 1e3 * t_total / args.steps
-    per_step = w.passes + 1
-    fwd_ms = [e0.elapsed_time(e1) for i, (e0, e1) in enumerate(events) if i % per_step != w.passes]
-    com_ms = [e0.elapsed_time(e1) for i, (e0, e1) in enumerate(events) if i % per_step == w.passes]
+    # readout launch time: span of the `passes` back-to-back launches of a step / passes;
+    # commit time: from the end of a step's last readout pass to the start of the next step
+    fwd_ms = [e0.elapsed_time(e1) / w.passes for (e0, e1) in events]
+    nxt = [e[0] for e in events[1:]] + [end]
+    com_ms = [events[i][1].elapsed_time(nxt[i]) for i in range(len(events))]
     fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
     com_avg_ms = sum(com_ms) / len(com_ms)
 

@@ -237,3 +237,56 @@ def test_wan_rollout_64_chained_commits(lib, oracle):
             print(f"[wan_rollout] chunk {c}: state err {e:.3e}", flush=True)
         assert e <= TOL_STATE, f"chunk {c}: state {e:.3e}"
     print(f"[wan_rollout] worst state err over 64 chained commits {worst:.3e}", flush=True)
+
+
+def test_softmax_over_full_kv_cache_shape(lib, oracle):
+    """Layers that keep softmax over a KV cache: one 4680-token chunk of queries against the cache of a
+    21-latent-frame horizon (32760 keys), no state.  Sampled rows against the oracle."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["wan_layer"], name="kv_cache_full")
+    Lq, Lkv = 4680, 32760
+    q = W.normal(5, w, (1, Lq, w.H, w.D), 1)
+    k = W.normal(5, w, (1, Lkv, w.H, w.D), 2)
+    v = W.normal(5, w, (1, Lkv, w.H, w.D), 3)
+    rows = sample_rows(Lq, 16, seed=11, block=256)
+    got = to_np(gpu_fwd(lib, q, k, v, None, None))[:, rows]
+    e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), rows=rows))
+    print(f"[kv_cache_full] Lq={Lq} Lkv={Lkv}: out err {e:.3e} on {len(rows)} rows/head", flush=True)
+    assert e <= TOL_BF16_OUT
+
+
+def test_rollout_step_latency_is_flat(lib):
+    """Per-chunk cost does not grow with the number of chunks already generated: the state has a
+    fixed size.  64 chunk steps (4 readout passes + 1 commit) at the headline shape, timed with
+    events on the launch stream; the same inputs are reused so that only the state evolves."""
+    w = W.WORKLOADS["wan_rollout"]
+    passes = [tuple(dev(t) for t in W.pass_inputs(w, 0, p)) for p in range(w.passes)]
+    kc, vc, gate = (dev(t) for t in W.clean_inputs(w, 0))
+    out = torch.empty_like(passes[0][0])
+    S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype)
+
+    def step():
+        for (q, k, v, g) in passes:
+            lib.arl2_hybrid_attn_fwd(q, k, v, S, g, out)
+        lib.arl2_state_commit(kc, vc, gate, S, ws)
+
+    for _ in range(30):          # clocks and caches settle
+        step()
+    S.zero_()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(w.chunks + 1)]
+    ev[0].record()
+    for c in range(w.chunks):
+        step()
+        ev[c + 1].record()
+    torch.cuda.synchronize()
+    ms = np.array([ev[c].elapsed_time(ev[c + 1]) for c in range(w.chunks)])
+    med = float(np.median(ms))
+    slope = float(np.polyfit(np.arange(w.chunks), ms, 1)[0])
+    print(f"[wan_rollout] step latency over {w.chunks} chunks: median {med:.4f} ms, max/median {ms.max() / med:.3f}, "
+          f"min/median {ms.min() / med:.3f}, least-squares drift over the rollout {slope * w.chunks / med * 100:+.2f} % of median",
+          flush=True)
+    print("[wan_rollout] ms per chunk:", " ".join(f"{x:.3f}" for x in ms), flush=True)
+    assert slope * w.chunks < 0.05 * med, "per-chunk latency grows with the chunk index"
+    assert np.percentile(ms, 90) < 1.15 * med
+    assert torch.isfinite(S).all()
