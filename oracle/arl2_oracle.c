@@ -20,6 +20,8 @@
  *     k'_i    = k_i / sqrt(|k_i|^2 + eps)               Eq. (3)
  *     S      <- gate * S + sum_i k'_i^T v_i             Eq. (4) with beta = 1 and the
  *                                                       delta-correction term dropped
+ *   commit, delta-rule variant (Eq. (4) literally, frame level):
+ *     S      <- alpha * S + beta * K'^T (V - K' S)
  *
  * Layouts (all contiguous, row-major):
  *   q [B][Lq][H][D], k,v [B][Lkv][H][D], g [B][Lq][H], out [B][nrows][H][D],
@@ -175,6 +177,62 @@ int arl2o_commit_f64(int B, int H, int L, int D,
             for (int d = 0; d < D; ++d)
                 for (int e = 0; e < D; ++e)
                     S_bh[(size_t)d * D + e] = a * S_bh[(size_t)d * D + e] + acc[(size_t)d * D + e];
+            free(acc);
+        }
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Frame-level gated delta rule, Eq. (4) taken literally with one (alpha, beta) pair per
+ * (stream, head):
+ *     S_new = alpha * S_old + beta * K'^T (V - K' S_old)
+ * Every token's correction term uses the same pre-update state S_old (frame-level access,
+ * Sec. 3.3); the gate multiplies the old state only.  In place.
+ */
+int arl2o_commit_delta_f64(int B, int H, int L, int D,
+                           const float *k, const float *v,
+                           const double *alpha, const double *beta,
+                           double l2_eps, double *S)
+{
+    const size_t ts = (size_t)H * D;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S_bh = S + ((size_t)b * H + h) * D * D;
+            const float *k_bh = k + ((size_t)b * L * H + h) * D;
+            const float *v_bh = v + ((size_t)b * L * H + h) * D;
+            /* acc[d][e] = sum_i k'_i[d] * u_i[e],  u_i = v_i - k'_i S_old */
+            double *acc = (double *)calloc((size_t)D * D + 2 * (size_t)D, sizeof(double));
+            if (!acc) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            double *kp = acc + (size_t)D * D;          /* normalised key row, Eq. (3) */
+            double *u = kp + D;                        /* value minus what the old state predicts */
+            for (int i = 0; i < L; ++i) {
+                double n2 = 0.0;
+                for (int d = 0; d < D; ++d)
+                    n2 += (double)k_bh[i * ts + d] * (double)k_bh[i * ts + d];
+                const double nk = sqrt(n2 + l2_eps);
+                for (int d = 0; d < D; ++d)
+                    kp[d] = (double)k_bh[i * ts + d] / nk;
+                for (int e = 0; e < D; ++e) {
+                    double pred = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        pred += kp[d] * S_bh[(size_t)d * D + e];
+                    u[e] = (double)v_bh[i * ts + e] - pred;
+                }
+                for (int d = 0; d < D; ++d)
+                    for (int e = 0; e < D; ++e)
+                        acc[(size_t)d * D + e] += kp[d] * u[e];
+            }
+            const double a = alpha[(size_t)b * H + h], bt = beta[(size_t)b * H + h];
+            for (int d = 0; d < D; ++d)
+                for (int e = 0; e < D; ++e)
+                    S_bh[(size_t)d * D + e] = a * S_bh[(size_t)d * D + e] + bt * acc[(size_t)d * D + e];
             free(acc);
         }
     }

@@ -50,6 +50,8 @@ def _load():
         lib.arl2o_fwd_f32.restype = i32
         lib.arl2o_commit_f32.argtypes = [i32] * 4 + [vp] * 3 + [f32, vp]
         lib.arl2o_commit_f32.restype = i32
+        lib.arl2o_commit_delta_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
+        lib.arl2o_commit_delta_f64.restype = i32
         lib.arl2o_num_threads.restype = i32
         _lib = lib
     return _lib
@@ -130,6 +132,24 @@ def commit(k, v, gate, S, *, l2_eps: float = L2_EPS, precision: str = "f64") -> 
     rc = fn(B, H, L, D, _ptr(k), _ptr(v), _ptr(gate), float(l2_eps), _ptr(S_new))
     if rc != 0:
         raise MemoryError("oracle commit failed")
+    return S_new
+
+
+def commit_delta(k, v, alpha, beta, S, *, l2_eps: float = L2_EPS) -> np.ndarray:
+    """Frame-level gated delta rule, Eq. (4) literally: alpha * S + beta * K'^T (V - K' S), every
+    token's correction using the same pre-update S.  fp64; returns a new array."""
+    lib = _load()
+    k, v = _c(k, np.float32), _c(v, np.float32)
+    if k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("k, v must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    alpha, beta = _c(alpha, np.float64), _c(beta, np.float64)
+    S_new = np.array(S, dtype=np.float64, order="C", copy=True)
+    if alpha.shape != (B, H) or beta.shape != (B, H) or S_new.shape != (B, H, D, D):
+        raise ValueError("alpha, beta must be [B, H] and S [B, H, D, D]")
+    rc = lib.arl2o_commit_delta_f64(B, H, L, D, _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), float(l2_eps), _ptr(S_new))
+    if rc != 0:
+        raise MemoryError("oracle commit_delta failed")
     return S_new
 
 

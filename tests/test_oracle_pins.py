@@ -285,3 +285,58 @@ def test_stored_bf16_values_reach_the_oracle_exactly():
     assert torch.equal(q, q2)
     q3, _, _, _ = W.pass_inputs(w, 0, 1)
     assert not torch.equal(q, q3)
+
+
+# ---------------------------------------------------------------- delta-rule commit (Eq. (4) literally)
+
+def test_delta_commit_matches_expanded_form(oracle):
+    """alpha S + beta K'^T (V - K' S) = (alpha I - beta K'^T K') S + beta K'^T V, via einsum."""
+    B, H, L, D = 2, 2, 19, 8
+    k, v = rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    alpha, beta = rng.uniform(0.8, 1.0, (B, H)), rng.uniform(0.05, 0.3, (B, H))
+    eps = oracle.L2_EPS
+    kn = l2n(k, eps)
+    G = np.einsum("blhd,blhe->bhde", kn, kn)
+    M = np.einsum("blhd,blhe->bhde", kn, v.astype(np.float64))
+    want = alpha[..., None, None] * S - beta[..., None, None] * np.einsum("bhdj,bhje->bhde", G, S) + beta[..., None, None] * M
+    np.testing.assert_allclose(oracle.commit_delta(k, v, alpha, beta, S), want, rtol=1e-11, atol=1e-12)
+
+
+def test_delta_commit_special_cases(oracle):
+    B, H, L, D = 1, 2, 13, 8
+    k, v = rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    alpha, beta = rng.uniform(0.8, 1.0, (B, H)), rng.uniform(0.05, 0.3, (B, H))
+    # beta = 0: only the decay remains
+    np.testing.assert_allclose(oracle.commit_delta(k, v, alpha, np.zeros((B, H)), S), alpha[..., None, None] * S, rtol=1e-14)
+    # zero state: no correction term, so it is beta times the plain outer-product sum
+    plain = oracle.commit(k, v, np.zeros((B, H)), np.zeros_like(S))
+    np.testing.assert_allclose(oracle.commit_delta(k, v, alpha, beta, np.zeros_like(S)), beta[..., None, None] * plain, rtol=1e-12, atol=1e-14)
+    # the input state is left untouched
+    snap = S.copy()
+    oracle.commit_delta(k, v, alpha, beta, S)
+    assert np.array_equal(S, snap)
+
+
+def test_delta_rule_overwrites_the_stored_value(oracle):
+    """One token, alpha = beta = 1: whatever the old state held, querying the key now returns v
+    exactly (k' S_new = k' S + (k' k'^T)(v - k' S) = v).  The plain rule would return k' S + v."""
+    D = 8
+    k, v = rand(1, 1, 1, D), rand(1, 1, 1, D)
+    S = rng.standard_normal((1, 1, D, D))
+    one = np.ones((1, 1))
+    S_new = oracle.commit_delta(k, v, one, one, S, l2_eps=0.0)
+    kn = l2n(k, 0.0)[0, 0, 0]
+    np.testing.assert_allclose(kn @ S_new[0, 0], v[0, 0, 0].astype(np.float64), rtol=1e-6, atol=1e-6)
+    S_plain = oracle.commit(k, v, one, S, l2_eps=0.0)
+    assert np.abs(kn @ S_plain[0, 0] - v[0, 0, 0]).max() > 1e-2
+
+
+def test_delta_commit_hand_example(oracle):
+    ex = json.load(open(os.path.join(HERE, "golden", "hand_example.json")))["commit_delta"]
+    k = np.array(ex["k"])[None, :, None, :]
+    v = np.array(ex["v"])[None, :, None, :]
+    S_old = np.array(ex["S_old"])[None, None]
+    S_new = oracle.commit_delta(k, v, np.array([[ex["alpha"]]]), np.array([[ex["beta"]]]), S_old, l2_eps=ex["l2_eps"])
+    np.testing.assert_allclose(S_new[0, 0], np.array(ex["S_new"]), rtol=0, atol=1e-12)
