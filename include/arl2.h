@@ -16,6 +16,8 @@
  *                          (Eq. (4) with beta = 1 and without the delta-correction term;
  *                           the gate multiplies the old state only).
  *
+ *   arl2_state_commit_delta the same update with Eq. (4)'s delta-correction term and learning rate.
+ *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
  * x / sqrt(sum x^2 + l2_eps), and V' = v.
@@ -68,8 +70,9 @@ typedef struct {
     void *stream;         /* hipStream_t; NULL is the default stream                        */
 } arl2_desc;
 
-/* Device scratch that arl2_state_commit needs for this descriptor (token-split partial
- * sums).  arl2_hybrid_attn_fwd needs none.  Returns 0 for an invalid descriptor.          */
+/* Device scratch that arl2_state_commit / arl2_state_commit_delta need for this descriptor
+ * (token-split partial sums, state snapshot).  arl2_hybrid_attn_fwd needs none.  Returns 0 for
+ * an invalid descriptor.                                                                     */
 size_t arl2_workspace_bytes(const arl2_desc *desc);
 
 /*
@@ -98,6 +101,23 @@ arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc,
 arl2_status arl2_state_commit(const arl2_desc *desc,
                               const void *k, const void *v,
                               const float *gate, float *S);
+
+/*
+ * Post-denoise state update with the delta-correction term: paper Eq. (4) taken literally at
+ * frame level,
+ *     S <- alpha * S + beta * K'^T (V - K' S),      K' = L2Norm(k) per token (Eq. (3)),
+ * every token's correction using the same pre-update S (frame-level access, Sec. 3.3).
+ *   k, v      device bf16 [B][Lq][H][D] of the clean pass (desc->io_dtype must be ARL2_BF16,
+ *             desc->Lkv must equal Lq); fp32 inputs return ARL2_ERR_UNSUPPORTED.
+ *   gate      device fp32 [B][H], the forget gate alpha.
+ *   beta      device fp32 [B][H], the learning rate.  With all L tokens written at once the update
+ *             is a contraction only for beta below about 2 D / L; that is the caller's choice.
+ *   S         device fp32 [B][H][D][D], updated IN PLACE.
+ * Deterministic like arl2_state_commit.  Uses desc->workspace (arl2_workspace_bytes covers it).
+ */
+arl2_status arl2_state_commit_delta(const arl2_desc *desc,
+                                    const void *k, const void *v,
+                                    const float *gate, const float *beta, float *S);
 
 const char *arl2_status_string(arl2_status s);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libarl2_hip.so")
 ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ERR_DEVICE = range(5)
 ARL2_F32, ARL2_BF16 = 0, 1
 
-EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit",
+EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
            "arl2_status_string", "arl2_last_error", "arl2_version"]
 
 
@@ -55,6 +55,8 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_hybrid_attn_fwd.restype = ctypes.c_int
         lib.arl2_state_commit.argtypes = [dp, vp, vp, vp, vp]
         lib.arl2_state_commit.restype = ctypes.c_int
+        lib.arl2_state_commit_delta.argtypes = [dp, vp, vp, vp, vp, vp]
+        lib.arl2_state_commit_delta.restype = ctypes.c_int
         lib.arl2_status_string.argtypes = [ctypes.c_int]
         lib.arl2_status_string.restype = ctypes.c_char_p
         lib.arl2_last_error.argtypes = []
@@ -147,6 +149,21 @@ def arl2_state_commit(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor, S: t
     st = load_library().arl2_state_commit(
         ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
         _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
+    _check(st)
+
+
+def arl2_state_commit_delta(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor, beta: torch.Tensor,
+                            S: torch.Tensor, workspace: torch.Tensor, *, l2_eps: float = 0.0,
+                            stream: Optional[int] = None) -> None:
+    """Delta-rule update of ``S`` in place (Eq. (4) literally), enqueued on the current (or given) stream."""
+    if k.dim() != 4:
+        raise ValueError("k must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, workspace=workspace, stream=stream)
+    st = load_library().arl2_state_commit_delta(
+        ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
+        _dev(gate, "gate", (B, H), torch.float32), _dev(beta, "beta", (B, H), torch.float32),
+        _dev(S, "S", (B, H, D, D), torch.float32))
     _check(st)
 
 

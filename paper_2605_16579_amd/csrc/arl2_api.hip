@@ -42,8 +42,8 @@ float resolved_eps(const arl2_desc *d) { return d->l2_eps > 0.f ? d->l2_eps : 1e
 
 size_t commit_workspace(const arl2_desc *d)
 {
-    if (d->io_dtype == ARL2_BF16)
-        return (size_t)d->B * d->H * arl2::commit_nsplit(d->B, d->H, d->Lq) * d->D * d->D * sizeof(float);
+    if (d->io_dtype == ARL2_BF16)   // two partial matrices per split (delta rule) plus one state snapshot
+        return (size_t)d->B * d->H * (2 * arl2::commit_nsplit(d->B, d->H, d->Lq) + 1) * d->D * d->D * sizeof(float);
     return (size_t)d->B * d->Lq * d->H * sizeof(float);
 }
 
@@ -84,22 +84,27 @@ arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const voi
     return ARL2_OK;
 }
 
-arl2_status arl2_state_commit(const arl2_desc *desc, const void *k, const void *v, const float *gate, float *S)
+static arl2_status commit_common(const arl2_desc *desc, const void *k, const void *v, const float *gate,
+                                 const float *beta, bool delta, float *S)
 {
     arl2_status st = check_desc(desc);
     if (st != ARL2_OK) return st;
-    if (!k || !v || !gate || !S) return fail(ARL2_ERR_INVALID_ARG, "k, v, gate and S must not be NULL");
+    if (!k || !v || !gate || !S || (delta && !beta))
+        return fail(ARL2_ERR_INVALID_ARG, "k, v, gate%s and S must not be NULL", delta ? ", beta" : "");
     if (!aligned16(k) || !aligned16(v) || !aligned16(S))
         return fail(ARL2_ERR_INVALID_ARG, "k, v and S must be 16-byte aligned");
-    if (reinterpret_cast<uintptr_t>(gate) & 3u) return fail(ARL2_ERR_INVALID_ARG, "gate must be 4-byte aligned");
-    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in arl2_state_commit");
+    if ((reinterpret_cast<uintptr_t>(gate) & 3u) || (reinterpret_cast<uintptr_t>(beta) & 3u))
+        return fail(ARL2_ERR_INVALID_ARG, "gate and beta must be 4-byte aligned");
+    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in a state commit");
+    if (delta && desc->io_dtype != ARL2_BF16)
+        return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_delta takes bf16 k, v only");
     const size_t need = commit_workspace(desc);
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
     if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
 
     arl2::CommitArgs a;
-    a.k = k; a.v = v; a.gate = gate; a.S = S; a.workspace = desc->workspace;
+    a.k = k; a.v = v; a.gate = gate; a.beta = delta ? beta : nullptr; a.S = S; a.workspace = desc->workspace;
     a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.D = desc->D;
     a.nsplit = arl2::commit_nsplit(desc->B, desc->H, desc->Lq);
     a.l2_eps = resolved_eps(desc);
@@ -108,6 +113,17 @@ arl2_status arl2_state_commit(const arl2_desc *desc, const void *k, const void *
                                                      : arl2::launch_commit_f32(a, stream);
     if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "commit launch failed: %s", hipGetErrorString(e));
     return ARL2_OK;
+}
+
+arl2_status arl2_state_commit(const arl2_desc *desc, const void *k, const void *v, const float *gate, float *S)
+{
+    return commit_common(desc, k, v, gate, nullptr, false, S);
+}
+
+arl2_status arl2_state_commit_delta(const arl2_desc *desc, const void *k, const void *v, const float *gate,
+                                    const float *beta, float *S)
+{
+    return commit_common(desc, k, v, gate, beta, true, S);
 }
 
 const char *arl2_status_string(arl2_status s)

@@ -14,6 +14,12 @@
 // flight while it works on the current one and finally writes a D x D fp32 partial to the workspace.
 // A second kernel adds the partials in split order and applies the gate to the old state, so the
 // result is bit-identical from run to run (no floating-point atomics).
+//
+// Delta-rule variant (Eq. (4) literally, frame level):
+//   S <- alpha S + beta K'^T (V - K' S) = alpha S + beta (K'^T V - (K'^T K') S)
+// needs no [L x D] intermediate: the same pass over the tokens also accumulates the Gram matrix
+// K'^T K' (raw K against r_i^2 k_i split into hi + lo), and the reduce kernel multiplies the summed
+// Gram matrix with a snapshot of the old state in fp32.
 #include "arl2_device.h"
 
 namespace arl2 {
@@ -36,23 +42,26 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <int D>
+template <int D, bool DELTA>
 struct CommitCfg {
     static constexpr int CPR = D / 8;                   // 16-byte chunks per row
     static constexpr int ROW = 2 * D + 64;              // LDS bytes per tile row (conflict-free transposing reads)
     static constexpr int MAT = BT * ROW;                // one 64-token tile
-    static constexpr int STAGE = 3 * MAT;               // K, V' hi, V' lo
+    static constexpr int NMAT = DELTA ? 5 : 3;          // K, V' hi, V' lo (, K'' hi, K'' lo with K'' = r^2 k)
+    static constexpr int STAGE = NMAT * MAT;
+    static constexpr int NSTG = DELTA ? 1 : 2;          // LDS stages (160 KB of LDS hold two 3-matrix stages or one 5-matrix stage)
+    static constexpr int NACC = DELTA ? 2 : 1;          // accumulated D x D matrices
     static constexpr int KCH = BT * CPR / NT;           // chunks per thread per tile (K and V each)
     static constexpr int ROWS_PER_PASS = NT / CPR;
     static constexpr int HB = D / 64;                   // 64-wide halves per dimension
     static constexpr int WAVES_USED = HB * HB;          // wavefronts that own a 64 x 64 output quadrant
 };
 
-template <int D>
+template <int D, bool DELTA>
 __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
 {
-    using C = CommitCfg<D>;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE];
+    using C = CommitCfg<D, DELTA>;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[C::NSTG * C::STAGE];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
@@ -99,6 +108,7 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
             }
 #pragma unroll
             for (int off = 1; off < C::CPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+            const float rn2 = 1.0f / (ss + a.l2_eps);
             const float rn = 1.0f / sqrtf(ss + a.l2_eps);
             union { u32x4 u; bf16x8 v; } vh, vl;
 #pragma unroll
@@ -115,6 +125,21 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
             *(u32x4 *)(p) = kr[i];
             *(u32x4 *)(p + C::MAT) = vh.u;
             *(u32x4 *)(p + 2 * C::MAT) = vl.u;
+            if constexpr (DELTA) {
+                union { u32x4 u; bf16x8 v; } kh, kl;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float s0 = __uint_as_float(kr[i][w] << 16) * rn2;
+                    const float s1 = __uint_as_float(kr[i][w] & 0xffff0000u) * rn2;
+                    const bf16_t h0 = to_bf16(s0), h1 = to_bf16(s1);
+                    kh.v[2 * w] = h0;
+                    kh.v[2 * w + 1] = h1;
+                    kl.v[2 * w] = to_bf16(s0 - (float)h0);
+                    kl.v[2 * w + 1] = to_bf16(s1 - (float)h1);
+                }
+                *(u32x4 *)(p + 3 * C::MAT) = kh.u;
+                *(u32x4 *)(p + 4 * C::MAT) = kl.u;
+            }
         }
     };
 
@@ -122,57 +147,116 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
     const bool compute = wave < C::WAVES_USED;
     const int d0 = 2 * (wave / C::HB), e0 = 2 * (wave % C::HB);
     const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
-    f32x16 acc[2][2];
+    f32x16 acc[C::NACC][2][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int m = 0; m < C::NACC; ++m)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[m][i][j][r] = 0.f;
+
+    if constexpr (DELTA) {
+        // the reduce kernel multiplies the Gram matrix with the old state while it overwrites S:
+        // split 0 of every (stream, head) leaves a snapshot of the old state in the workspace
+        if (split == 0) {
+            const f32x4 *src = (const f32x4 *)(a.S + (size_t)bh * D * D);
+            f32x4 *dst = (f32x4 *)((float *)a.workspace + (size_t)a.B * H * a.nsplit * 2 * D * D + (size_t)bh * D * D);
+            for (int i = tid; i < D * D / 4; i += NT) dst[i] = src[i];
+        }
+    }
 
     if (t_begin < t_end) load_tile();
     for (int tile = t_begin; tile < t_end; ++tile) {
-        const int stage = (tile - t_begin) & 1;
+        const int stage = C::NSTG == 2 ? ((tile - t_begin) & 1) : 0;
+        if constexpr (C::NSTG == 1) __syncthreads();   // single stage: the previous tile's MFMAs are done
         stage_tile(stage);               // waits for this tile's loads
-        __syncthreads();                 // also: every wave is done with the MFMAs of the tile before last
+        __syncthreads();                 // two stages: every wave is also done with the tile before last
         if (tile + 1 < t_end) load_tile();
         if (compute) {
             const unsigned char *sm = smem + stage * C::STAGE + tr_off;
 #pragma unroll
             for (int t = 0; t < BT / 16; ++t) {
                 const unsigned char *row = sm + 16 * t * C::ROW;     // tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
-                bf16x8 ka[2], vh[2], vl[2];
+                bf16x8 ka[2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    ka[i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
-                    vh[i] = lds_read_tr_pair(row + C::MAT + 64 * (e0 + i), 8 * C::ROW);
-                    vl[i] = lds_read_tr_pair(row + 2 * C::MAT + 64 * (e0 + i), 8 * C::ROW);
-                }
+                for (int i = 0; i < 2; ++i) ka[i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int m = 0; m < C::NACC; ++m) {      // m = 0: K^T V',  m = 1: K^T K''
+                    bf16x8 bh_[2], bl_[2];
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], vh[j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], vl[j], acc[i][j], 0, 0, 0);
+                        bh_[j] = lds_read_tr_pair(row + (1 + 2 * m) * C::MAT + 64 * (e0 + j), 8 * C::ROW);
+                        bl_[j] = lds_read_tr_pair(row + (2 + 2 * m) * C::MAT + 64 * (e0 + j), 8 * C::ROW);
                     }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            acc[m][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], bh_[j], acc[m][i][j], 0, 0, 0);
+                            acc[m][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], bl_[j], acc[m][i][j], 0, 0, 0);
+                        }
+                }
             }
         }
     }
 
-    // partial[bh][split][d][e]
+    // partial[bh][split][matrix][d][e]
     if (compute) {
-        float *part = (float *)a.workspace + ((size_t)bh * a.nsplit + split) * D * D;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int m = 0; m < C::NACC; ++m) {
+            float *part = (float *)a.workspace + (((size_t)bh * a.nsplit + split) * C::NACC + m) * D * D;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int d = 32 * (d0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const int e = 32 * (e0 + j) + (lane & 31);
-                    part[(size_t)d * D + e] = acc[i][j][r];
-                }
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int d = 32 * (d0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+                        const int e = 32 * (e0 + j) + (lane & 31);
+                        part[(size_t)d * D + e] = acc[m][i][j][r];
+                    }
+        }
     }
+}
+
+// Delta rule: S[bh] = alpha S_old + beta (M - G S_old) with M, G the split-ordered sums of the two
+// partial matrices and S_old the snapshot taken by the partial kernel.  One workgroup owns 8 rows d.
+template <int D>
+__global__ __launch_bounds__(NT) void commit_delta_reduce_kernel(CommitArgs a)
+{
+    constexpr int ROWS = NT / (D / 4);                // rows per workgroup (8 for D = 128, 16 for D = 64)
+    __shared__ float Gs[ROWS][D];
+    const int wg_per_head = D / ROWS;
+    const int bh = blockIdx.x / wg_per_head;
+    const int r = threadIdx.x / (D / 4), e4 = threadIdx.x % (D / 4);
+    const int d = (blockIdx.x % wg_per_head) * ROWS + r;
+    const size_t dd = (size_t)D * D;
+    const float *part = (const float *)a.workspace + (size_t)bh * a.nsplit * 2 * dd + (size_t)d * D + 4 * e4;
+    const float *Sold = (const float *)a.workspace + (size_t)a.B * a.H * a.nsplit * 2 * dd + (size_t)bh * dd;
+    f32x4 m = {0.f, 0.f, 0.f, 0.f}, g = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.nsplit; ++s) {
+        const f32x4 pm = *(const f32x4 *)(part + (size_t)s * 2 * dd);
+        const f32x4 pg = *(const f32x4 *)(part + (size_t)s * 2 * dd + dd);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { m[c] += pm[c]; g[c] += pg[c]; }
+    }
+    *(f32x4 *)&Gs[r][4 * e4] = g;
+    __syncthreads();
+    f32x4 t = {0.f, 0.f, 0.f, 0.f};                    // (G S_old)[d][4 e4 .. +3]
+    for (int j = 0; j < D; ++j) {
+        const float gj = Gs[r][j];
+        const f32x4 sj = *(const f32x4 *)(Sold + (size_t)j * D + 4 * e4);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) t[c] = fmaf(gj, sj[c], t[c]);
+    }
+    const float alpha = a.gate[bh], beta = a.beta[bh];
+    const f32x4 old = *(const f32x4 *)(Sold + (size_t)d * D + 4 * e4);
+    f32x4 res;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) res[c] = fmaf(alpha, old[c], beta * (m[c] - t[c]));
+    *(f32x4 *)(a.S + (size_t)bh * dd + (size_t)d * D + 4 * e4) = res;
 }
 
 // S[bh] = gate[bh] * S[bh] + sum_{split ascending} partial[bh][split]
@@ -225,14 +309,28 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
     // the kernel addresses one stream's K (or V) with 32-bit byte offsets
     if ((long long)(a.L + 4 * BT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.D == 128)
-        hipLaunchKernelGGL(commit_partial_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+    const bool delta = a.beta != nullptr;
+    if (a.D == 128 && !delta)
+        hipLaunchKernelGGL((commit_partial_kernel<128, false>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+    else if (a.D == 64 && !delta)
+        hipLaunchKernelGGL((commit_partial_kernel<64, false>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+    else if (a.D == 128)
+        hipLaunchKernelGGL((commit_partial_kernel<128, true>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else if (a.D == 64)
-        hipLaunchKernelGGL(commit_partial_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL((commit_partial_kernel<64, true>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else
         return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (delta) {
+        const int rows = NT / (a.D / 4);
+        const long long rwg = (long long)a.B * a.H * (a.D / rows);
+        if (a.D == 128)
+            hipLaunchKernelGGL(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NT), 0, stream, a);
+        else
+            hipLaunchKernelGGL(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NT), 0, stream, a);
+        return hipGetLastError();
+    }
     const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
     const long long rwg = (long long)a.B * a.H * (vec_per_head / NT);
     hipLaunchKernelGGL(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NT), 0, stream, a, vec_per_head);

@@ -36,7 +36,8 @@ struct FwdArgs {
 
 struct CommitArgs {
     const void *k, *v;
-    const float *gate;
+    const float *gate;     // forget gate alpha
+    const float *beta;     // nullptr: plain commit; else the delta rule's learning rate
     float *S;
     void *workspace;
     int B, H, L, D;

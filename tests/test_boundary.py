@@ -90,6 +90,14 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     assert call(d, gate=0x3002) == 1
     d.Lkv = 32
     assert call(d) == 1
+    # delta-rule variant: needs beta, and bf16 inputs
+    d.Lkv = 64
+    delta = lambda d, beta=0x5000: lib.arl2_state_commit_delta(ctypes.byref(d), 0x1000, 0x2000, 0x3000, beta, 0x4000)
+    assert delta(d, beta=None) == 1
+    assert delta(d, beta=0x5002) == 1
+    df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
+    df.workspace, df.workspace_bytes = 0x10000, 1 << 20
+    assert delta(df) == 2
 
 
 def test_binding_refuses_host_tensors(A):

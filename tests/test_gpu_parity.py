@@ -290,3 +290,53 @@ def test_rollout_step_latency_is_flat(lib):
     assert slope * w.chunks < 0.05 * med, "per-chunk latency grows with the chunk index"
     assert np.percentile(ms, 90) < 1.15 * med
     assert torch.isfinite(S).all()
+
+
+@pytest.mark.parametrize("D,L", [(128, 328), (64, 200), (128, 64), (128, 1)])
+def test_delta_rule_commit_small(lib, oracle, D, L):
+    """Eq. (4) with the delta-correction term, element by element, three chained updates."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"delta{D}", D=D, L=L)
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    for c in range(3):
+        k, v, alpha = W.clean_inputs(w, c)
+        beta = W.uniform(0, w, (w.B, w.H), 0.2 * D / max(L, D), 1.0 * D / max(L, D), c, 0, 77)
+        S_ref = oracle.commit_delta(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+        lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        assert e <= TOL_STATE, f"D={D} L={L} update {c}: {e:.3e}"
+
+
+def test_delta_rule_commit_full_size(lib, oracle):
+    """Headline shape: state pre-filled by plain commits, then four chained delta-rule updates with
+    beta in the range where the frame-level rule is a contraction (below 2 D / L)."""
+    w = W.WORKLOADS["wan_layer"]
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    for j in range(2):
+        k, v, gate = W.prefill_inputs(w, j)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+        lib.arl2_state_commit(dev(k), dev(v), dev(gate), S_dev, ws)
+    worst = 0.0
+    for c in range(4):
+        k, v, alpha = W.clean_inputs(w, c)
+        beta = W.uniform(0, w, (w.B, w.H), 0.2 * w.D / w.L, 1.0 * w.D / w.L, c, 0, 77)
+        S_ref = oracle.commit_delta(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+        lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        worst = max(worst, e)
+        assert e <= TOL_STATE, f"update {c}: {e:.3e}"
+    print(f"[wan_layer] delta-rule commit, worst state err over 4 chained updates {worst:.3e}", flush=True)
+    # deterministic
+    S2 = S_dev.clone()
+    k, v, alpha = W.clean_inputs(w, 9)
+    beta = W.uniform(0, w, (w.B, w.H), 0.005, 0.02, 9, 0, 77)
+    lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+    lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(S_dev, S2)
