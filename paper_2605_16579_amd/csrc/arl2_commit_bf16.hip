@@ -11,7 +11,9 @@
 // from the K registers on their way to LDS (lane shuffles across the 16 lanes that share a row).
 //
 // Tokens are split over `nsplit` workgroups per (stream, head); each keeps the next tile's loads in
-// flight while it works on the current one and finally writes a D x D fp32 partial to the workspace.
+// flight while it works on the current one (8 wavefronts, each a 64 x 32 block of the partial, operand
+// fragments of the next 16-token step requested before the MFMAs of the current one) and finally
+// writes a D x D fp32 partial to the workspace.
 // A second kernel adds the partials in split order and applies the gate to the old state, so the
 // result is bit-identical from run to run (no floating-point atomics).
 //
@@ -26,7 +28,8 @@ namespace arl2 {
 namespace {
 
 constexpr int BT = 64;    // tokens per tile
-constexpr int NT = 256;
+constexpr int NT = 512;    // partial kernel: 8 wavefronts, two per SIMD
+constexpr int NTR = 256;   // reduce kernels
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
@@ -53,12 +56,14 @@ struct CommitCfg {
     static constexpr int NACC = DELTA ? 2 : 1;          // accumulated D x D matrices
     static constexpr int KCH = BT * CPR / NT;           // chunks per thread per tile (K and V each)
     static constexpr int ROWS_PER_PASS = NT / CPR;
-    static constexpr int HB = D / 64;                   // 64-wide halves per dimension
-    static constexpr int WAVES_USED = HB * HB;          // wavefronts that own a 64 x 64 output quadrant
+    static constexpr int DH = D / 64;                   // 64-row halves of the output
+    static constexpr int EB = D / 32;                   // 32-column blocks of the output
+    static constexpr int WAVES_USED = DH * EB;          // wavefronts that own a 64 x 32 output block (8 for D = 128)
+    static_assert(KCH >= 1, "tile too small for the workgroup");
 };
 
 template <int D, bool DELTA>
-__global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
+__global__ __launch_bounds__(NT, 2) void commit_partial_kernel(CommitArgs a)
 {
     using C = CommitCfg<D, DELTA>;
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::NSTG * C::STAGE];
@@ -143,19 +148,17 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
         }
     };
 
-    // this wavefront's 64 x 64 quadrant of the D x D partial: feature blocks d0, d0+1 x e0, e0+1
+    // this wavefront's 64 x 32 block of the D x D partial: feature blocks d0, d0+1 x e0
     const bool compute = wave < C::WAVES_USED;
-    const int d0 = 2 * (wave / C::HB), e0 = 2 * (wave % C::HB);
+    const int d0 = 2 * (wave / C::EB), e0 = wave % C::EB;
     const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
-    f32x16 acc[C::NACC][2][2];
+    f32x16 acc[C::NACC][2];
 #pragma unroll
     for (int m = 0; m < C::NACC; ++m)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[m][i][j][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[m][i][r] = 0.f;
 
     if constexpr (DELTA) {
         // the reduce kernel multiplies the Gram matrix with the old state while it overwrites S:
@@ -176,28 +179,29 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
         if (tile + 1 < t_end) load_tile();
         if (compute) {
             const unsigned char *sm = smem + stage * C::STAGE + tr_off;
+            // operand fragments of 16-token step t: tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
+            bf16x8 ka[2][2], bh_[2][C::NACC], bl_[2][C::NACC];
+            auto load_step = [&](int t, int buf) {
+                const unsigned char *row = sm + 16 * t * C::ROW;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) ka[buf][i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
+#pragma unroll
+                for (int m = 0; m < C::NACC; ++m) {      // m = 0: r V,  m = 1: r^2 K
+                    bh_[buf][m] = lds_read_tr_pair(row + (1 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
+                    bl_[buf][m] = lds_read_tr_pair(row + (2 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
+                }
+            };
+            load_step(0, 0);
 #pragma unroll
             for (int t = 0; t < BT / 16; ++t) {
-                const unsigned char *row = sm + 16 * t * C::ROW;     // tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
-                bf16x8 ka[2];
+                if (t + 1 < BT / 16) load_step(t + 1, (t + 1) & 1);
 #pragma unroll
-                for (int i = 0; i < 2; ++i) ka[i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
+                for (int m = 0; m < C::NACC; ++m)
 #pragma unroll
-                for (int m = 0; m < C::NACC; ++m) {      // m = 0: K^T V',  m = 1: K^T K''
-                    bf16x8 bh_[2], bl_[2];
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        bh_[j] = lds_read_tr_pair(row + (1 + 2 * m) * C::MAT + 64 * (e0 + j), 8 * C::ROW);
-                        bl_[j] = lds_read_tr_pair(row + (2 + 2 * m) * C::MAT + 64 * (e0 + j), 8 * C::ROW);
+                    for (int i = 0; i < 2; ++i) {
+                        acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bh_[t & 1][m], acc[m][i], 0, 0, 0);
+                        acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bl_[t & 1][m], acc[m][i], 0, 0, 0);
                     }
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            acc[m][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], bh_[j], acc[m][i][j], 0, 0, 0);
-                            acc[m][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], bl_[j], acc[m][i][j], 0, 0, 0);
-                        }
-                }
             }
         }
     }
@@ -210,13 +214,11 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int d = 32 * (d0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        const int e = 32 * (e0 + j) + (lane & 31);
-                        part[(size_t)d * D + e] = acc[m][i][j][r];
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int d = 32 * (d0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int e = 32 * e0 + (lane & 31);
+                    part[(size_t)d * D + e] = acc[m][i][r];
+                }
         }
     }
 }
@@ -224,9 +226,9 @@ __global__ __launch_bounds__(NT, 1) void commit_partial_kernel(CommitArgs a)
 // Delta rule: S[bh] = alpha S_old + beta (M - G S_old) with M, G the split-ordered sums of the two
 // partial matrices and S_old the snapshot taken by the partial kernel.  One workgroup owns 8 rows d.
 template <int D>
-__global__ __launch_bounds__(NT) void commit_delta_reduce_kernel(CommitArgs a)
+__global__ __launch_bounds__(NTR) void commit_delta_reduce_kernel(CommitArgs a)
 {
-    constexpr int ROWS = NT / (D / 4);                // rows per workgroup (8 for D = 128, 16 for D = 64)
+    constexpr int ROWS = NTR / (D / 4);                // rows per workgroup (8 for D = 128, 16 for D = 64)
     __shared__ float Gs[ROWS][D];
     const int wg_per_head = D / ROWS;
     const int bh = blockIdx.x / wg_per_head;
@@ -261,10 +263,10 @@ __global__ __launch_bounds__(NT) void commit_delta_reduce_kernel(CommitArgs a)
 
 // S[bh] = gate[bh] * S[bh] + sum_{split ascending} partial[bh][split]
 template <int NS>
-__global__ __launch_bounds__(NT) void commit_reduce_kernel(CommitArgs a, int vec_per_head)
+__global__ __launch_bounds__(NTR) void commit_reduce_kernel(CommitArgs a, int vec_per_head)
 {
-    const int bh = blockIdx.x / (vec_per_head / NT);
-    const int vi = (blockIdx.x % (vec_per_head / NT)) * NT + threadIdx.x;
+    const int bh = blockIdx.x / (vec_per_head / NTR);
+    const int vi = (blockIdx.x % (vec_per_head / NTR)) * NTR + threadIdx.x;
     const size_t head_elems = (size_t)vec_per_head * 4;
     const f32x4 *part = (const f32x4 *)((const float *)a.workspace + (size_t)bh * a.nsplit * head_elems) + vi;
     f32x4 *Sg = (f32x4 *)(a.S + (size_t)bh * head_elems);
@@ -323,17 +325,17 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (delta) {
-        const int rows = NT / (a.D / 4);
+        const int rows = NTR / (a.D / 4);
         const long long rwg = (long long)a.B * a.H * (a.D / rows);
         if (a.D == 128)
-            hipLaunchKernelGGL(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NT), 0, stream, a);
+            hipLaunchKernelGGL(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a);
         else
-            hipLaunchKernelGGL(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NT), 0, stream, a);
+            hipLaunchKernelGGL(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a);
         return hipGetLastError();
     }
     const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
-    const long long rwg = (long long)a.B * a.H * (vec_per_head / NT);
-    hipLaunchKernelGGL(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NT), 0, stream, a, vec_per_head);
+    const long long rwg = (long long)a.B * a.H * (vec_per_head / NTR);
+    hipLaunchKernelGGL(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a, vec_per_head);
     return hipGetLastError();
 }
 
