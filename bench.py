@@ -68,6 +68,61 @@ def cpu_baseline(w, passes_inputs, clean, S0, steps):
     }
 
 
+def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5):
+    """Attention-only time and memory of a full layer stack over a 7-chunk (21 latent frame) rollout.
+    Every layer pass is one arl2_hybrid_attn_fwd call at the Wan-2.1-1.3B layer shape: hybrid layers
+    read the fixed-size state; softmax layers attend to a KV cache that holds c chunks at chunk c
+    (S = NULL, Lkv = c * 4680).  Layer passes of one kind and one cache length cost the same, so each
+    distinct call is timed once (median of `reps`) and the stack total is the weighted sum; inputs are
+    synthetic and there is no model between the layers."""
+    w = W.WORKLOADS["wan_layer"]
+    P = w.passes
+    q, k, v, g = (t.to(dev) for t in W.pass_inputs(w, 0, 0))
+    kc, vc, gate = (t.to(dev) for t in W.clean_inputs(w, 0))
+    out = torch.empty_like(q)
+    S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
+    ws = A.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype, device=dev)
+    A.arl2_state_commit(kc, vc, gate, S, ws)
+    kv_k = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 101).to(dev)
+    kv_v = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 102).to(dev)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return sorted(ts)[len(ts) // 2]
+
+    t_hybrid = timed(lambda: A.arl2_hybrid_attn_fwd(q, k, v, S, g, out))
+    t_commit = timed(lambda: A.arl2_state_commit(kc, vc, gate, S, ws))
+    t_kv = [timed(lambda c=c: A.arl2_hybrid_attn_fwd(q, kv_k[:, :c * w.L], kv_v[:, :c * w.L], None, None, out))
+            for c in range(1, chunks + 1)]
+    sm_layers = layers - hybrid_layers
+    hybrid_ms = sum(P * (hybrid_layers * t_hybrid + sm_layers * t_kv[c]) + hybrid_layers * t_commit for c in range(chunks))
+    softmax_ms = sum(P * layers * t_kv[c] for c in range(chunks))
+    tok_bytes = w.B * w.H * w.D * 2
+    kv_layer_bytes = 2 * chunks * w.L * tok_bytes                      # K and V cache of one softmax layer at full length
+    state_bytes = w.B * w.H * w.D * w.D * 4
+    return {
+        "report": "attention time and memory of a %d-layer stack over %d chunks of %d tokens, %d readout passes per chunk"
+                  % (layers, chunks, w.L, P),
+        "hybrid_stack": {"layers": "%d hybrid + %d softmax-KV" % (hybrid_layers, sm_layers), "attention_ms": hybrid_ms,
+                         "memory_bytes": hybrid_layers * state_bytes + sm_layers * kv_layer_bytes},
+        "softmax_stack": {"layers": "%d softmax-KV" % layers, "attention_ms": softmax_ms,
+                          "memory_bytes": layers * kv_layer_bytes},
+        "speedup": softmax_ms / hybrid_ms,
+        "memory_ratio": (hybrid_layers * state_bytes + sm_layers * kv_layer_bytes) / (layers * kv_layer_bytes),
+        "per_call_ms": {"hybrid_pass": t_hybrid, "commit": t_commit, "softmax_kv_pass_by_cached_chunks": t_kv},
+        "note": "the paper's 2.26x / -54% are end-to-end (denoising + VAE) on another GPU; this is attention only",
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +131,9 @@ def main() -> int:
     ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
     ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack-report", action="store_true",
+                    help="instead of the bench line: attention time and memory of a 30-layer stack over a "
+                         "21-latent-frame rollout (7 chunks), 22 hybrid + 8 softmax-KV layers vs 30 softmax-KV layers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (5 times): the reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -107,6 +165,9 @@ def main() -> int:
         return 0
     w = W.WORKLOADS[args.workload]
     io_bytes = 2 if w.io_dtype == "bf16" else 4
+    if args.stack_report:
+        print(json.dumps(stack_report(A, W, torch, dev)), flush=True)
+        return 0
 
     # ---- inputs, resident in HBM
     passes_cpu = [W.pass_inputs(w, 0, p) for p in range(w.passes)]
