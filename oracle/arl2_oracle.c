@@ -239,6 +239,58 @@ int arl2o_commit_delta_f64(int B, int H, int L, int D,
     return fail ? -1 : 0;
 }
 
+/*
+ * Token-sequential gated delta rule: Eq. (4) applied to one token at a time, in token order, with
+ * per-token gates (Sec. 3.2, the remark after Eq. (4); Alg. 1, clean pass).  For j = 1..L
+ *     S_j = alpha_j * S_{j-1} + beta_j * k'_j^T (v_j - k'_j S_{j-1}),
+ * the correction of token j reading the state as token j-1 left it.  alpha, beta: [B][L][H].
+ * In place: S holds S_L on return.
+ */
+int arl2o_commit_gdn_f64(int B, int H, int L, int D,
+                         const float *k, const float *v,
+                         const double *alpha, const double *beta,
+                         double l2_eps, double *S)
+{
+    const size_t ts = (size_t)H * D;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S_bh = S + ((size_t)b * H + h) * D * D;
+            const float *k_bh = k + ((size_t)b * L * H + h) * D;
+            const float *v_bh = v + ((size_t)b * L * H + h) * D;
+            double *kp = (double *)malloc(2 * (size_t)D * sizeof(double));
+            if (!kp) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            double *u = kp + D;
+            for (int j = 0; j < L; ++j) {
+                const double a = alpha[((size_t)b * L + j) * H + h];
+                const double bt = beta[((size_t)b * L + j) * H + h];
+                double n2 = 0.0;
+                for (int d = 0; d < D; ++d)
+                    n2 += (double)k_bh[j * ts + d] * (double)k_bh[j * ts + d];
+                const double nk = sqrt(n2 + l2_eps);
+                for (int d = 0; d < D; ++d)
+                    kp[d] = (double)k_bh[j * ts + d] / nk;
+                for (int e = 0; e < D; ++e) {          /* u = v_j - k'_j S_{j-1} */
+                    double pred = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        pred += kp[d] * S_bh[(size_t)d * D + e];
+                    u[e] = (double)v_bh[j * ts + e] - pred;
+                }
+                for (int d = 0; d < D; ++d)
+                    for (int e = 0; e < D; ++e)
+                        S_bh[(size_t)d * D + e] = a * S_bh[(size_t)d * D + e] + bt * kp[d] * u[e];
+            }
+            free(kp);
+        }
+    }
+    return fail ? -1 : 0;
+}
+
 /* ---------------------------------------------------------------- fp32 -- */
 /* The same two definitions with every operation in float: the reference for
  * the configuration that is specified as fp32 throughout.                    */

@@ -52,6 +52,8 @@ def _load():
         lib.arl2o_commit_f32.restype = i32
         lib.arl2o_commit_delta_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
         lib.arl2o_commit_delta_f64.restype = i32
+        lib.arl2o_commit_gdn_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
+        lib.arl2o_commit_gdn_f64.restype = i32
         lib.arl2o_num_threads.restype = i32
         _lib = lib
     return _lib
@@ -150,6 +152,24 @@ def commit_delta(k, v, alpha, beta, S, *, l2_eps: float = L2_EPS) -> np.ndarray:
     rc = lib.arl2o_commit_delta_f64(B, H, L, D, _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), float(l2_eps), _ptr(S_new))
     if rc != 0:
         raise MemoryError("oracle commit_delta failed")
+    return S_new
+
+
+def commit_gdn(k, v, alpha, beta, S, *, l2_eps: float = L2_EPS) -> np.ndarray:
+    """Token-sequential gated delta rule (Eq. (4) per token, in token order, per-token gates
+    alpha, beta of shape [B, L, H]).  fp64; returns a new array."""
+    lib = _load()
+    k, v = _c(k, np.float32), _c(v, np.float32)
+    if k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("k, v must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    alpha, beta = _c(alpha, np.float64), _c(beta, np.float64)
+    S_new = np.array(S, dtype=np.float64, order="C", copy=True)
+    if alpha.shape != (B, L, H) or beta.shape != (B, L, H) or S_new.shape != (B, H, D, D):
+        raise ValueError("alpha, beta must be [B, L, H] and S [B, H, D, D]")
+    rc = lib.arl2o_commit_gdn_f64(B, H, L, D, _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), float(l2_eps), _ptr(S_new))
+    if rc != 0:
+        raise MemoryError("oracle commit_gdn failed")
     return S_new
 
 

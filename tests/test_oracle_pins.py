@@ -340,3 +340,137 @@ def test_delta_commit_hand_example(oracle):
     S_old = np.array(ex["S_old"])[None, None]
     S_new = oracle.commit_delta(k, v, np.array([[ex["alpha"]]]), np.array([[ex["beta"]]]), S_old, l2_eps=ex["l2_eps"])
     np.testing.assert_allclose(S_new[0, 0], np.array(ex["S_new"]), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- token-sequential gated delta rule
+
+def _gdn_inputs(B, H, L, D, lo=0.7):
+    k, v = rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    alpha, beta = rng.uniform(lo, 1.0, (B, L, H)), rng.uniform(0.1, 0.9, (B, L, H))
+    return k, v, alpha, beta, S
+
+
+def test_gdn_commit_hand_example(oracle):
+    ex = json.load(open(os.path.join(HERE, "golden", "hand_example.json")))["commit_gdn"]
+    k = np.array(ex["k"])[None, :, None, :]
+    v = np.array(ex["v"])[None, :, None, :]
+    a = np.array(ex["alpha"])[None, :, None]
+    b = np.array(ex["beta"])[None, :, None]
+    S_new = oracle.commit_gdn(k, v, a, b, np.array(ex["S_old"])[None, None], l2_eps=ex["l2_eps"])
+    np.testing.assert_allclose(S_new[0, 0], np.array(ex["S_new"]), rtol=0, atol=1e-12)
+
+
+def test_gdn_commit_single_token_is_the_frame_level_rule(oracle):
+    """With L = 1 'sequential over the tokens' and 'all tokens against the old state' coincide."""
+    B, H, D = 2, 3, 8
+    k, v, alpha, beta, S = _gdn_inputs(B, H, 1, D)
+    want = oracle.commit_delta(k, v, alpha[:, 0], beta[:, 0], S)
+    np.testing.assert_allclose(oracle.commit_gdn(k, v, alpha, beta, S), want, rtol=1e-13, atol=1e-14)
+
+
+def test_gdn_commit_transition_matrix_product(oracle):
+    """Each token is the affine map S -> (alpha I - beta k'^T k') S + beta k'^T v; compose them with
+    explicit matrices (catches a correction that reads the wrong state or a gate on the wrong term)."""
+    B, H, L, D = 1, 2, 23, 6
+    k, v, alpha, beta, S = _gdn_inputs(B, H, L, D)
+    kn = l2n(k, oracle.L2_EPS)
+    got = oracle.commit_gdn(k, v, alpha, beta, S)
+    for h in range(H):
+        P, Q = np.eye(D), np.zeros((D, D))
+        for j in range(L):
+            kj = kn[0, j, h][None, :]
+            Tj = alpha[0, j, h] * np.eye(D) - beta[0, j, h] * kj.T @ kj
+            P, Q = Tj @ P, Tj @ Q + beta[0, j, h] * kj.T @ v[0, j, h][None, :].astype(np.float64)
+        np.testing.assert_allclose(got[0, h], P @ S[0, h] + Q, rtol=1e-11, atol=1e-12)
+
+
+def test_gdn_commit_orthonormal_keys_closed_form(oracle):
+    """Mutually orthogonal keys do not see each other's writes, so every correction reads only the
+    decayed initial state: S_L = g_L S_0 + sum_j (prod_{m>j} alpha_m) beta_j k_j^T (v_j - g_{j-1} k_j S_0)."""
+    D = L = 8
+    Qm, _ = np.linalg.qr(rng.standard_normal((D, D)))
+    k = (Qm * rng.uniform(0.5, 3.0, (L, 1))).astype(np.float32)[None, :, None, :]     # rows: scaled orthonormal
+    v = rand(1, L, 1, D)
+    S = rng.standard_normal((1, 1, D, D))
+    alpha, beta = rng.uniform(0.6, 1.0, (1, L, 1)), rng.uniform(0.1, 0.9, (1, L, 1))
+    kn = l2n(k, 0.0)[0, :, 0]
+    a, b = alpha[0, :, 0], beta[0, :, 0]
+    g = np.concatenate([[1.0], np.cumprod(a)])            # g[j] = alpha_1 ... alpha_j
+    want = g[L] * S[0, 0]
+    for j in range(L):
+        tail = np.prod(a[j + 1:])
+        want = want + tail * b[j] * np.outer(kn[j], v[0, j, 0].astype(np.float64) - g[j] * (kn[j] @ S[0, 0]))
+    np.testing.assert_allclose(oracle.commit_gdn(k, v, alpha, beta, S, l2_eps=0.0)[0, 0], want, rtol=1e-6, atol=1e-6)
+
+
+def _gdn_chunkwise(kn, v, a, b, S, C):
+    """Blocked evaluation of the same recurrence (an algebraically different route): inside a block of
+    C tokens the pseudo-values w_i = beta_i (v_i - k_i S_{i-1}) solve a unit lower-triangular system,
+    after which the block is one affine map of the state."""
+    L, D = kn.shape
+    for c0 in range(0, L, C):
+        K, V, al, be = kn[c0:c0 + C], v[c0:c0 + C], a[c0:c0 + C], b[c0:c0 + C]
+        n = K.shape[0]
+        gam = np.concatenate([[1.0], np.cumprod(al)])     # gam[i] = alpha_1..alpha_i inside the block
+        A = np.zeros((n, n))
+        for i in range(n):
+            for j in range(i):
+                A[i, j] = be[i] * np.prod(al[j + 1:i]) * (K[i] @ K[j])
+        rhs = be[:, None] * V - (be * gam[:n])[:, None] * (K @ S)
+        Wp = np.linalg.solve(np.eye(n) + A, rhs)
+        tail = np.array([np.prod(al[j + 1:]) for j in range(n)])
+        S = gam[n] * S + (tail[:, None] * K).T @ Wp
+    return S
+
+
+@pytest.mark.parametrize("C", [1, 4, 7, 64])
+def test_gdn_commit_matches_blocked_evaluation(oracle, C):
+    B, H, L, D = 1, 2, 37, 8
+    k, v, alpha, beta, S = _gdn_inputs(B, H, L, D)
+    got = oracle.commit_gdn(k, v, alpha, beta, S)
+    kn = l2n(k, oracle.L2_EPS)
+    for h in range(H):
+        want = _gdn_chunkwise(kn[0, :, h], v[0, :, h].astype(np.float64), alpha[0, :, h], beta[0, :, h], S[0, h], C)
+        np.testing.assert_allclose(got[0, h], want, rtol=1e-10, atol=1e-11)
+
+
+def test_gdn_commit_special_cases(oracle):
+    B, H, L, D = 1, 2, 11, 8
+    k, v, alpha, beta, S = _gdn_inputs(B, H, L, D)
+    # beta = 0 everywhere: only the product of the per-token forget gates remains
+    got = oracle.commit_gdn(k, v, alpha, np.zeros_like(beta), S)
+    np.testing.assert_allclose(got, alpha.prod(axis=1)[..., None, None] * S, rtol=1e-13)
+    # alpha = beta = 1, eps = 0: the last token's value is stored exactly under its key
+    one = np.ones_like(alpha)
+    got = oracle.commit_gdn(k, v, one, one, S, l2_eps=0.0)
+    kn = l2n(k, 0.0)
+    for h in range(H):
+        np.testing.assert_allclose(kn[0, -1, h] @ got[0, h], v[0, -1, h].astype(np.float64), rtol=1e-6, atol=1e-6)
+    # a gate of zero at the last token leaves only that token's write, a rank-one matrix whose
+    # correction term still saw the state before it (the gate multiplies the old state only)
+    a0 = alpha.copy()
+    a0[:, -1] = 0.0
+    got = oracle.commit_gdn(k, v, a0, beta, S)
+    before = oracle.commit_gdn(k[:, :-1], v[:, :-1], alpha[:, :-1], beta[:, :-1], S)
+    kn = l2n(k, oracle.L2_EPS)
+    for h in range(H):
+        kl = kn[0, -1, h]
+        want = beta[0, -1, h] * np.outer(kl, v[0, -1, h].astype(np.float64) - kl @ before[0, h])
+        np.testing.assert_allclose(got[0, h], want, rtol=1e-12, atol=1e-13)
+    # the input state is left untouched; token order matters (it is not the frame-level rule)
+    snap = S.copy()
+    fwd_order = oracle.commit_gdn(k, v, alpha, beta, S)
+    assert np.array_equal(S, snap)
+    rev = oracle.commit_gdn(k[:, ::-1], v[:, ::-1], alpha[:, ::-1], beta[:, ::-1], S)
+    assert np.abs(fwd_order - rev).max() > 1e-3
+
+
+def test_gdn_commit_splits_into_consecutive_calls(oracle):
+    """Committing tokens 1..L in one call equals committing 1..m and then m+1..L."""
+    B, H, L, D = 2, 2, 21, 8
+    k, v, alpha, beta, S = _gdn_inputs(B, H, L, D)
+    whole = oracle.commit_gdn(k, v, alpha, beta, S)
+    m = 8
+    half = oracle.commit_gdn(k[:, :m], v[:, :m], alpha[:, :m], beta[:, :m], S)
+    np.testing.assert_allclose(oracle.commit_gdn(k[:, m:], v[:, m:], alpha[:, m:], beta[:, m:], half), whole, rtol=1e-13, atol=1e-14)
