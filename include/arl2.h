@@ -18,6 +18,8 @@
  *
  *   arl2_state_commit_delta the same update with Eq. (4)'s delta-correction term and learning rate.
  *
+ *   arl2_state_commit_gdn  Eq. (4) applied token by token in order, with per-token gates.
+ *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
  * x / sqrt(sum x^2 + l2_eps), and V' = v.
@@ -118,6 +120,25 @@ arl2_status arl2_state_commit(const arl2_desc *desc,
 arl2_status arl2_state_commit_delta(const arl2_desc *desc,
                                     const void *k, const void *v,
                                     const float *gate, const float *beta, float *S);
+
+/*
+ * Token-sequential gated delta rule: paper Eq. (4) applied to one token at a time, in token order,
+ * with per-token gates (Sec. 3.2, remark after Eq. (4); Alg. 1, clean pass).  For j = 1..Lq
+ *     S <- alpha_j * S + beta_j * k'_j^T (v_j - k'_j S),      k'_j = L2Norm(k_j)  (Eq. (3)),
+ * the correction of token j reading the state as token j-1 left it.
+ *   k, v      device bf16 [B][Lq][H][D] of the clean pass (desc->io_dtype must be ARL2_BF16,
+ *             desc->Lkv must equal Lq); fp32 inputs return ARL2_ERR_UNSUPPORTED.
+ *   alpha     device fp32 [B][Lq][H], per-token forget gates.
+ *   beta      device fp32 [B][Lq][H], per-token learning rates; each step is a contraction for
+ *             0 <= beta_j <= 1 and 0 <= alpha_j <= 1.
+ *   S         device fp32 [B][H][D][D], updated IN PLACE.
+ * desc->workspace must hold arl2_gdn_workspace_bytes(desc) bytes (the transition maps of all blocks
+ * of 64 tokens; about 128 KiB per block and head at D = 128).  Deterministic.
+ */
+size_t arl2_gdn_workspace_bytes(const arl2_desc *desc);
+arl2_status arl2_state_commit_gdn(const arl2_desc *desc,
+                                  const void *k, const void *v,
+                                  const float *alpha, const float *beta, float *S);
 
 const char *arl2_status_string(arl2_status s);
 

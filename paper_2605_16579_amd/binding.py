@@ -19,7 +19,7 @@ ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ER
 ARL2_F32, ARL2_BF16 = 0, 1
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
-           "arl2_status_string", "arl2_last_error", "arl2_version"]
+           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_status_string", "arl2_last_error", "arl2_version"]
 
 
 class arl2_desc(ctypes.Structure):
@@ -57,6 +57,10 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_state_commit.restype = ctypes.c_int
         lib.arl2_state_commit_delta.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_state_commit_delta.restype = ctypes.c_int
+        lib.arl2_gdn_workspace_bytes.argtypes = [dp]
+        lib.arl2_gdn_workspace_bytes.restype = ctypes.c_size_t
+        lib.arl2_state_commit_gdn.argtypes = [dp, vp, vp, vp, vp, vp]
+        lib.arl2_state_commit_gdn.restype = ctypes.c_int
         lib.arl2_status_string.argtypes = [ctypes.c_int]
         lib.arl2_status_string.restype = ctypes.c_char_p
         lib.arl2_last_error.argtypes = []
@@ -163,6 +167,27 @@ def arl2_state_commit_delta(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor
     st = load_library().arl2_state_commit_delta(
         ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
         _dev(gate, "gate", (B, H), torch.float32), _dev(beta, "beta", (B, H), torch.float32),
+        _dev(S, "S", (B, H, D, D), torch.float32))
+    _check(st)
+
+
+def arl2_gdn_workspace_bytes(B: int, H: int, L: int, D: int) -> int:
+    d = make_desc(B, H, L, L, D, ARL2_BF16, stream=0)
+    return int(load_library().arl2_gdn_workspace_bytes(ctypes.byref(d)))
+
+
+def arl2_state_commit_gdn(k: torch.Tensor, v: torch.Tensor, alpha: torch.Tensor, beta: torch.Tensor,
+                          S: torch.Tensor, workspace: torch.Tensor, *, l2_eps: float = 0.0,
+                          stream: Optional[int] = None) -> None:
+    """Token-sequential gated delta rule on ``S`` in place (Eq. (4) per token, per-token gates
+    ``alpha``, ``beta`` of shape [B, L, H]), enqueued on the current (or given) stream."""
+    if k.dim() != 4:
+        raise ValueError("k must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, workspace=workspace, stream=stream)
+    st = load_library().arl2_state_commit_gdn(
+        ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
+        _dev(alpha, "alpha", (B, L, H), torch.float32), _dev(beta, "beta", (B, L, H), torch.float32),
         _dev(S, "S", (B, H, D, D), torch.float32))
     _check(st)
 

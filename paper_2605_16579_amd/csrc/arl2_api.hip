@@ -126,6 +126,40 @@ arl2_status arl2_state_commit_delta(const arl2_desc *desc, const void *k, const 
     return commit_common(desc, k, v, gate, beta, true, S);
 }
 
+size_t arl2_gdn_workspace_bytes(const arl2_desc *desc)
+{
+    if (check_desc(desc) != ARL2_OK) return 0;
+    return arl2::gdn_workspace_bytes(desc->B, desc->H, desc->Lq, desc->D);
+}
+
+arl2_status arl2_state_commit_gdn(const arl2_desc *desc, const void *k, const void *v, const float *alpha,
+                                  const float *beta, float *S)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!k || !v || !alpha || !beta || !S)
+        return fail(ARL2_ERR_INVALID_ARG, "k, v, alpha, beta and S must not be NULL");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(S))
+        return fail(ARL2_ERR_INVALID_ARG, "k, v and S must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(alpha) & 3u) || (reinterpret_cast<uintptr_t>(beta) & 3u))
+        return fail(ARL2_ERR_INVALID_ARG, "alpha and beta must be 4-byte aligned");
+    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in a state commit");
+    if (desc->io_dtype != ARL2_BF16)
+        return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_gdn takes bf16 k, v only");
+    const size_t need = arl2::gdn_workspace_bytes(desc->B, desc->H, desc->Lq, desc->D);
+    if (desc->workspace == nullptr || desc->workspace_bytes < need)
+        return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_gdn_workspace_bytes()");
+    if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+
+    arl2::GdnArgs a;
+    a.k = k; a.v = v; a.alpha = alpha; a.beta = beta; a.S = S; a.workspace = desc->workspace;
+    a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.D = desc->D;
+    a.l2_eps = resolved_eps(desc);
+    const hipError_t e = arl2::launch_commit_gdn_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "gdn commit launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
 const char *arl2_status_string(arl2_status s)
 {
     switch (s) {

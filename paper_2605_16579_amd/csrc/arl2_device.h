@@ -45,6 +45,16 @@ struct CommitArgs {
     float l2_eps;
 };
 
+struct GdnArgs {
+    const void *k, *v;
+    const float *alpha;    // per-token forget gate  [B][L][H]
+    const float *beta;     // per-token learning rate [B][L][H]
+    float *S;
+    void *workspace;
+    int B, H, L, D;
+    float l2_eps;
+};
+
 // Token splits used by the bf16 commit for a problem size (also sizes the workspace).
 int commit_nsplit(int B, int H, int L);
 
@@ -53,6 +63,10 @@ hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream);
 hipError_t launch_fwd_f32(const FwdArgs &a, hipStream_t stream);
 hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream);
+hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream);
+
+// Workspace of the token-sequential commit (per-block transition maps).
+size_t gdn_workspace_bytes(int B, int H, int L, int D);
 
 // ---- small device helpers -------------------------------------------------------------
 

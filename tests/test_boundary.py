@@ -98,6 +98,18 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
     df.workspace, df.workspace_bytes = 0x10000, 1 << 20
     assert delta(df) == 2
+    # token-sequential variant: its own workspace size, per-token gates, bf16 inputs
+    gdn = lambda d, alpha=0x3000, beta=0x5000: lib.arl2_state_commit_gdn(ctypes.byref(d), 0x1000, 0x2000, alpha, beta, 0x4000)
+    need = A.arl2_gdn_workspace_bytes(1, 2, 64, 64)
+    assert need == 2 * (64 * 64 * 8 + 16)
+    assert A.arl2_gdn_workspace_bytes(1, 2, 65, 64) == 2 * need
+    d.workspace_bytes = need - 1
+    assert gdn(d) == 3                                    # one byte short
+    d.workspace_bytes = need
+    assert gdn(d, alpha=None) == 1
+    assert gdn(d, beta=0x5002) == 1
+    df.workspace_bytes = 1 << 24
+    assert gdn(df) == 2
 
 
 def test_binding_refuses_host_tensors(A):

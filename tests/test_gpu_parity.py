@@ -340,3 +340,81 @@ def test_delta_rule_commit_full_size(lib, oracle):
     lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S2, ws)
     torch.cuda.synchronize()
     assert torch.equal(S_dev, S2)
+
+
+# ---------------------------------------------------------------- token-sequential gated delta rule
+
+def _gdn_ws(lib, w):
+    return torch.empty(lib.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("D,L", [(128, 328), (64, 200), (128, 64), (128, 65), (64, 63), (128, 1)])
+def test_gdn_commit_small(lib, oracle, D, L):
+    """Eq. (4) token by token with per-token gates, element by element, three chained updates;
+    sizes below, at and above one 64-token block, both head dimensions."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gdn{D}", D=D, L=L)
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    ws = _gdn_ws(lib, w)
+    for c in range(3):
+        k, v, _ = W.clean_inputs(w, c)
+        alpha, beta = W.token_gates(w, c)
+        S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+        lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        assert e <= TOL_STATE, f"D={D} L={L} update {c}: {e:.3e}"
+
+
+def test_gdn_commit_gate_edge_values(lib, oracle):
+    """Gates of exactly 0 and 1 and learning rates of exactly 0 and 1 inside and across blocks."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="gdn_edges", L=200)
+    k, v, _ = W.clean_inputs(w, 0)
+    alpha, beta = W.token_gates(w, 0)
+    alpha[:, 5] = 0.0
+    alpha[:, 63] = 0.0
+    alpha[:, 64] = 1.0
+    alpha[0, 130:140] = 0.0
+    beta[:, 7] = 0.0
+    beta[:, 100] = 1.0
+    beta[1, 64:128] = 0.0
+    S0 = W.normal(3, w, (w.B, w.H, w.D, w.D), 0, 0, 91, io_dtype="f32")
+    S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), to_np(S0).astype(np.float64))
+    S_dev = dev(S0).clone()
+    lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, _gdn_ws(lib, w))
+    torch.cuda.synchronize()
+    assert torch.isfinite(S_dev).all()
+    e = rel_err_per_head(to_np(S_dev), S_ref)
+    assert e <= TOL_STATE, f"{e:.3e}"
+
+
+def test_gdn_commit_full_size(lib, oracle):
+    """Headline shape: four chained token-sequential updates of a pre-filled state."""
+    w = W.WORKLOADS["wan_layer"]
+    S_ref = np.zeros((w.B, w.H, w.D, w.D))
+    S_dev = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    ws_plain = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    ws = _gdn_ws(lib, w)
+    for j in range(2):
+        k, v, gate = W.prefill_inputs(w, j)
+        S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
+        lib.arl2_state_commit(dev(k), dev(v), dev(gate), S_dev, ws_plain)
+    worst = 0.0
+    for c in range(4):
+        k, v, _ = W.clean_inputs(w, c)
+        alpha, beta = W.token_gates(w, c)
+        S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+        lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        worst = max(worst, e)
+        assert e <= TOL_STATE, f"update {c}: {e:.3e}"
+    print(f"[wan_layer] token-sequential commit, worst state err over 4 chained updates {worst:.3e}", flush=True)
+    # deterministic
+    S2 = S_dev.clone()
+    lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+    lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(S_dev, S2)

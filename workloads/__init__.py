@@ -82,7 +82,7 @@ def uniform(seed: int, w: Workload, shape, lo: float, hi: float, *ids: int) -> t
 
 
 # tensor tags
-_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE = range(10)
+_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE, _TALPHA, _TBETA = range(12)
 
 
 def pass_inputs(w: Workload, chunk: int, p: int, seed: int = 0
@@ -114,6 +114,19 @@ def prefill_inputs(w: Workload, j: int, seed: int = 0
     v = normal(seed, w, shp, j, 0, _PV)
     gate = uniform(seed, w, (w.B, w.H), w.gate_lo, w.gate_hi, j, 0, _PGATE)
     return k, v, gate
+
+
+def token_gates(w: Workload, chunk: int, seed: int = 0) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Per-token forget gates and learning rates [B,L,H] fp32 for the token-sequential commit.
+
+    The forget gates of a chunk multiply to about the chunk-level gate of the same workload
+    (each is gate ** (2 u / L), u ~ U(0,1), gate ~ U(gate_lo, gate_hi) per stream and head);
+    the learning rates are U(0.05, 0.95), the open unit interval a sigmoid projection produces."""
+    gate = uniform(seed, w, (w.B, 1, w.H), w.gate_lo, w.gate_hi, chunk, 1, _GATE)
+    u = uniform(seed, w, (w.B, w.L, w.H), 0.0, 1.0, chunk, 0, _TALPHA)
+    alpha = torch.pow(gate, 2.0 * u / w.L).to(torch.float32).contiguous()
+    beta = uniform(seed, w, (w.B, w.L, w.H), 0.05, 0.95, chunk, 0, _TBETA)
+    return alpha, beta
 
 
 def as_f32_numpy(t: torch.Tensor) -> np.ndarray:
