@@ -15,11 +15,15 @@
 //
 // Kernel 1 (one workgroup per block of tokens, all blocks in parallel) builds -E (as bf16 hi + lo parts),
 // Psi (fp32) and gam.  The Gram matrix uses the raw bf16 keys (exact products) and is scaled in fp32;
-// the triangular solve runs in fp32 on the vector ALU, one thread per feature; the two contractions
-// over tokens run on MFMA with Z split into bf16 hi + lo against the raw bf16 K and V.
+// the triangular solve runs in fp32 on the vector ALU, one thread per feature (right-looking, so the
+// 63 updates after each solved row are independent); the two contractions over tokens run on MFMA with
+// Z split into bf16 hi + lo against the raw bf16 K and V.  -E is computed transposed: the accumulator
+// registers of (-E)^T are then exactly the A-operand fragments of -E that kernel 2 needs (k-slot j of
+// half-wave hh <-> column 16 t + 8 (j / 4) + 4 hh + j % 4), and are stored as such, 16 bytes per lane.
 // Kernel 2 walks the blocks in order: one workgroup per (stream, head, 32 state columns), the state
 // slice in accumulator registers, S <- gam S + Psi + (-E) S with -E hi/lo against S hi/lo (three MFMA
-// terms, the lo x lo term is below fp32 rounding), the slice exchanged between wavefronts through LDS.
+// terms, the lo x lo term is below fp32 rounding), the slice exchanged between wavefronts through LDS
+// in the same k-slot order.
 // All products of gates are formed by multiplication only, so gates of exactly zero are handled.
 #include "arl2_device.h"
 
@@ -30,6 +34,9 @@ namespace {
 
 constexpr int CT = 64;     // tokens per block
 constexpr int NTA = 256;   // threads of the block kernel
+#ifndef GDN_PFD
+#define GDN_PFD 2
+#endif
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
@@ -45,6 +52,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
+// Workgroup barrier that orders LDS traffic only: global stores issued before it stay in flight
+// (__syncthreads would first wait for them to complete).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F &&f)
 {
@@ -57,20 +71,23 @@ __device__ __forceinline__ void static_for(F &&f)
 template <int D>
 struct GdnCfg {
     static constexpr int CPR = D / 8;                   // 16-byte chunks per row
-    static constexpr int ROW = 2 * D + 32;              // LDS bytes per tile row
+    static constexpr int ROW = 2 * D + 32;              // LDS bytes per row of a token-major tile (K, V)
     static constexpr int TILE = CT * ROW;               // one 64-token bf16 tile
+    static constexpr int ZROW = 2 * CT + 16;            // LDS bytes per row of a feature-major tile (Z^T)
     static constexpr int KCH = CT * CPR / NTA;          // chunks per thread per tile
     static constexpr int ROWS_PER_PASS = NTA / CPR;
-    static constexpr int AST = 68;                      // floats per row of the 64 x 64 fp32 matrices
+    static constexpr int AST = 68;                      // floats per row of the 64 x 64 fp32 matrix
     static constexpr int NB = D / 32;                   // 32-wide blocks per side of a D x D matrix
+    static constexpr int KS = D / 16;                   // k-steps of a D-long contraction
     static constexpr int EPW = NB * NB / 4;             // output blocks per wavefront (all in one block row)
-    static constexpr int REG = TILE > CT * AST * 4 ? TILE : CT * AST * 4;   // a region holds a tile or a 64 x 64 fp32 matrix
+    static constexpr int REG = TILE > CT * AST * 4 ? TILE : CT * AST * 4;   // a region holds a tile or the fp32 matrix
     static constexpr int SC_OFF = 4 * REG;              // per-token scalars behind the four regions
-    static constexpr int SMEM = SC_OFF + 5 * CT * 4 + 16;
+    static constexpr int SMEM = SC_OFF + 8 * CT * 4 + 16;
+    static_assert(D * ZROW <= REG, "a feature-major tile must fit into one region");
     static_assert(KCH >= 1 && EPW >= 1, "unsupported head dimension");
 };
 
-// Bytes of workspace per block of tokens: -E hi, -E lo (bf16), Psi (fp32), gam (padded).
+// Workspace per block of tokens: -E hi, -E lo (bf16, fragment order), Psi (fp32, accumulator order), gam.
 __host__ __device__ constexpr size_t gdn_block_bytes(int D) { return (size_t)D * D * 8 + 16; }
 
 // ---- kernel 1: the affine map of one block of tokens -------------------------------------------------
@@ -81,7 +98,10 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];
     unsigned char *R0 = smem, *R1 = smem + C::REG, *R2 = smem + 2 * C::REG, *R3 = smem + 3 * C::REG;
     float *sc_r = (float *)(smem + C::SC_OFF);          // 1 / sqrt(|k_i|^2 + eps)
-    float *sc_al = sc_r + CT, *sc_be = sc_al + CT, *sc_gp = sc_be + CT, *sc_tl = sc_gp + CT, *sc_gam = sc_tl + CT;
+    float *sc_al = sc_r + CT, *sc_be = sc_al + CT;      // alpha_i, beta_i
+    float *sc_tr = sc_be + CT;                          // (alpha_{i+1} .. alpha_64) r_i
+    float *sc_se = sc_tr + CT;                          // -beta_i (alpha_1 .. alpha_{i-1}) r_i
+    float *sc_gam = sc_se + CT;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
@@ -134,13 +154,22 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
     }
     __syncthreads();
 
-    // ---- 2. products of gates (wavefront 0) and the Gram matrix of the raw keys (all wavefronts)
+    // ---- 2. products of gates (wavefront 0) and the Gram matrix of the raw keys (three wavefronts)
     if (tid < CT) {
-        float gp = 1.f, tl = 1.f;
-        for (int m = 0; m < tid; ++m) gp *= sc_al[m];
-        for (int m = tid + 1; m < CT; ++m) tl *= sc_al[m];
-        sc_gp[tid] = gp;
-        sc_tl[tid] = tl;
+        float gp = 1.f, tl = 1.f;                        // alpha_1 .. alpha_{i-1},  alpha_{i+1} .. alpha_64
+#pragma unroll
+        for (int q = 0; q < CT / 4; ++q) {
+            const f32x4 a4 = *(const f32x4 *)(sc_al + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int m = 4 * q + e;
+                gp *= m < tid ? a4[e] : 1.f;
+                tl *= m > tid ? a4[e] : 1.f;
+            }
+        }
+        const float r = sc_r[tid], be = sc_be[tid];
+        sc_tr[tid] = tl * r;
+        sc_se[tid] = -(be * gp * r);
         if (tid == CT - 1) sc_gam[0] = gp * sc_al[tid];
     }
     {
@@ -148,7 +177,7 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
         if (jb <= ib) {                                  // the strictly upper block is never used
             f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int t = 0; t < D / 16; ++t) {
+            for (int t = 0; t < C::KS; ++t) {
                 const bf16x8 ka = *(const bf16x8 *)(R0 + (32 * ib + c32) * C::ROW + 32 * t + 16 * hh);
                 const bf16x8 kb = *(const bf16x8 *)(R0 + (32 * jb + c32) * C::ROW + 32 * t + 16 * hh);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, kb, acc, 0, 0, 0);
@@ -163,109 +192,154 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
     }
     __syncthreads();
 
-    // ---- 3. At[j][i] = A_ij = beta_i (alpha_{j+1} .. alpha_{i-1}) r_i r_j G_ij  (i > j), thread = column j
-    if (tid < CT) {
-        const float *Gs = (const float *)R2;
-        float *At = (float *)R3;
-        const int j = tid;
+    // ---- 3. A_ij = beta_i (alpha_{j+1} .. alpha_{i-1}) r_i r_j G_ij for i > j, in place;
+    //         thread = (column j, rows 16 wave .. 16 wave + 15)
+    {
+        float *As = (float *)R2;
+        const int j = lane, i0 = 16 * wave;
+        float g[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) g[e] = As[(i0 + e) * C::AST + j];
+        float rho = 1.f;                                 // alpha_{j+1} .. alpha_{i0-1}
+#pragma unroll
+        for (int q = 0; q < 12; ++q) {
+            const f32x4 al4 = *(const f32x4 *)(sc_al + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rho *= (4 * q + e > j && 4 * q + e < i0) ? al4[e] : 1.f;
+        }
         const float rj = sc_r[j];
-        float rho = 1.f;
-        for (int i = j + 1; i < CT; ++i) {
-            At[j * C::AST + i] = sc_be[i] * rho * sc_r[i] * rj * Gs[i * C::AST + j];
-            rho *= sc_al[i];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 al4 = *(const f32x4 *)(sc_al + i0 + 4 * q);
+            const f32x4 be4 = *(const f32x4 *)(sc_be + i0 + 4 * q);
+            const f32x4 r4 = *(const f32x4 *)(sc_r + i0 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = i0 + 4 * q + e;
+                if (i > j) {
+                    As[i * C::AST + j] = be4[e] * rho * r4[e] * rj * g[4 * q + e];
+                    rho *= al4[e];
+                }
+            }
         }
     }
     __syncthreads();
 
-    // ---- 4. back substitution (I + A)^T Z = diag(tail r) K, thread = feature
+    // ---- 4. back substitution (I + A)^T Z = diag(tail r) K, thread = feature; row i of A updates rows j < i
     float z[CT];
     if (tid < D) {
-        const float *At = (const float *)R3;
-        static_for<0, CT>([&](auto ii_) {
-            constexpr int i = CT - 1 - decltype(ii_)::value;
-            float acc = sc_tl[i] * sc_r[i] * (float)*(const bf16_t *)(R0 + i * C::ROW + 2 * tid);
-            static_for<(i + 1) / 4, CT / 4>([&](auto q_) {
+        const float *As = (const float *)R2;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) z[i] = sc_tr[i] * (float)*(const bf16_t *)(R0 + i * C::ROW + 2 * tid);
+        static_for<0, CT - 1>([&](auto ii_) {
+            constexpr int i = CT - 1 - decltype(ii_)::value;       // z[i] is final; i = 63 .. 1
+            static_for<0, (i + 3) / 4>([&](auto q_) {
                 constexpr int q = decltype(q_)::value;
-                const f32x4 a4 = *(const f32x4 *)(At + i * C::AST + 4 * q);
+                const f32x4 a4 = *(const f32x4 *)(As + i * C::AST + 4 * q);
                 static_for<0, 4>([&](auto e_) {
                     constexpr int j = 4 * q + decltype(e_)::value;
-                    if constexpr (j > i) acc = fmaf(-a4[j - 4 * q], z[j], acc);
+                    if constexpr (j < i) z[j] = fmaf(-a4[j - 4 * q], z[i], z[j]);
                 });
             });
-            z[i] = acc;
         });
     }
-    __syncthreads();                                     // At and G are dead: R2, R3 become the Z tiles
+    __syncthreads();                                     // A is dead: R2, R3 become the Z^T tiles
 
-    // Z scaled per token, negated if asked, split into bf16 hi (R2) + lo (R3)
-    auto put_z = [&](bool for_e) {
+    // Z^T scaled per token (sc points at 64 scales), split into bf16 hi (R2) + lo (R3), [feature][token]
+    auto put_z = [&](const float *sc) {
         if (tid < D) {
 #pragma unroll
-            for (int i = 0; i < CT; ++i) {
-                const float s = for_e ? -(sc_be[i] * sc_gp[i] * sc_r[i]) : sc_be[i];
-                const float x = s * z[i];
-                const bf16_t hi = to_bf16(x);
-                *(bf16_t *)(R2 + i * C::ROW + 2 * tid) = hi;
-                *(bf16_t *)(R3 + i * C::ROW + 2 * tid) = to_bf16(x - (float)hi);
+            for (int q = 0; q < CT / 8; ++q) {
+                const f32x4 s0 = *(const f32x4 *)(sc + 8 * q), s1 = *(const f32x4 *)(sc + 8 * q + 4);
+                bf16x8 h8, l8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = (e < 4 ? s0[e] : s1[e - 4]) * z[8 * q + e];
+                    h8[e] = to_bf16(x);
+                    l8[e] = to_bf16(x - (float)h8[e]);
+                }
+                *(bf16x8 *)(R2 + tid * C::ZROW + 16 * q) = h8;
+                *(bf16x8 *)(R3 + tid * C::ZROW + 16 * q) = l8;
             }
         }
     };
-    // acc[n] = (Z tile)^T (X tile) for this wavefront's blocks: rows d in block dblk, columns in blocks eblk0 + n
+    // Operand fragments of 16-token step t.  A token-major tile is read through the transposing LDS read
+    // (k-slot j <-> token 16 t + 8 (j / 4) + 4 hh + j % 4); the feature-major Z^T tiles give the same order
+    // with two 8-byte reads.
     const int dblk = (wave * C::EPW) / C::NB, eblk0 = (wave * C::EPW) % C::NB;
     const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    const int z_off = (32 * dblk + c32) * C::ZROW + 8 * hh;
+    auto z_frag = [&](const unsigned char *Zt, int t) -> bf16x8 {
+        const bf16x4 lo = *(const bf16x4 *)(Zt + z_off + 32 * t);
+        const bf16x4 hi = *(const bf16x4 *)(Zt + z_off + 32 * t + 16);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
     f32x16 acc[C::EPW];
-    auto contract = [&](const unsigned char *X) {
+    auto clear_acc = [&]() {
 #pragma unroll
         for (int n = 0; n < C::EPW; ++n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
-#pragma unroll
-        for (int t = 0; t < CT / 16; ++t) {
-            const int row = tr_off + 16 * t * C::ROW;
-            const bf16x8 zh = lds_read_tr_pair(R2 + row + 64 * dblk, 8 * C::ROW);
-            const bf16x8 zl = lds_read_tr_pair(R3 + row + 64 * dblk, 8 * C::ROW);
-#pragma unroll
-            for (int n = 0; n < C::EPW; ++n) {
-                const bf16x8 xb = lds_read_tr_pair(X + row + 64 * (eblk0 + n), 8 * C::ROW);
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, xb, acc[n], 0, 0, 0);
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, xb, acc[n], 0, 0, 0);
-            }
-        }
     };
 
     unsigned char *out = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_block_bytes(D);
-    bf16_t *Ehi = (bf16_t *)out, *Elo = Ehi + D * D;
-    float *Psi = (float *)(out + (size_t)D * D * 4);
+    bf16x8 *Ehi = (bf16x8 *)out, *Elo = Ehi + D * D / 8;
+    f32x4 *Psi = (f32x4 *)(out + (size_t)D * D * 4);
     float *gam = (float *)(out + (size_t)D * D * 8);
 
-    // ---- 5. -E = (-diag(beta gamma- r) Z)^T K
-    put_z(true);
+    // ---- 5. (-E)^T = K^T (-diag(beta gamma- r) Z): rows e (blocks eblk0 + n), columns d (block dblk)
+    put_z(sc_se);
     __syncthreads();
-    contract(R0);
+    clear_acc();
 #pragma unroll
-    for (int n = 0; n < C::EPW; ++n)
+    for (int t = 0; t < CT / 16; ++t) {
+        const bf16x8 zh = z_frag(R2, t), zl = z_frag(R3, t);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int d = 32 * dblk + 8 * (r >> 2) + 4 * hh + (r & 3);
-            const int e = 32 * (eblk0 + n) + c32;
-            const float x = acc[n][r];
-            const bf16_t hi = to_bf16(x);
-            Ehi[d * D + e] = hi;
-            Elo[d * D + e] = to_bf16(x - (float)hi);
+        for (int n = 0; n < C::EPW; ++n) {
+            const bf16x8 ka = lds_read_tr_pair(R0 + tr_off + 16 * t * C::ROW + 64 * (eblk0 + n), 8 * C::ROW);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, zh, acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, zl, acc[n], 0, 0, 0);
         }
-    __syncthreads();                                     // every wavefront is done reading the Z tiles
-
-    // ---- 6. Psi = (diag(beta) Z)^T V
-    put_z(false);
-    __syncthreads();
-    contract(R1);
+    }
+    // accumulator registers 8 tt .. 8 tt + 7 of block n are lane (d, hh)'s A fragment of -E for k-step 2 (eblk0 + n) + tt
 #pragma unroll
     for (int n = 0; n < C::EPW; ++n)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int d = 32 * dblk + 8 * (r >> 2) + 4 * hh + (r & 3);
-            const int e = 32 * (eblk0 + n) + c32;
-            Psi[d * D + e] = acc[n][r];
+        for (int tt = 0; tt < 2; ++tt) {
+            bf16x8 h8, l8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x = acc[n][8 * tt + e];
+                h8[e] = to_bf16(x);
+                l8[e] = to_bf16(x - (float)h8[e]);
+            }
+            const int idx = (dblk * C::KS + 2 * (eblk0 + n) + tt) * 64 + lane;
+            Ehi[idx] = h8;
+            Elo[idx] = l8;
+        }
+    lds_barrier();                                       // every wavefront is done reading the Z^T tiles
+
+    // ---- 6. Psi = (diag(beta) Z)^T V: rows d (block dblk), columns e (blocks eblk0 + n)
+    put_z(sc_be);
+    lds_barrier();
+    clear_acc();
+#pragma unroll
+    for (int t = 0; t < CT / 16; ++t) {
+        const bf16x8 zh = z_frag(R2, t), zl = z_frag(R3, t);
+#pragma unroll
+        for (int n = 0; n < C::EPW; ++n) {
+            const bf16x8 vb = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * (eblk0 + n), 8 * C::ROW);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, vb, acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, vb, acc[n], 0, 0, 0);
+        }
+    }
+    // accumulator order of the scan kernel: [row block][column block][register quad][lane]
+#pragma unroll
+    for (int n = 0; n < C::EPW; ++n)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 x = {acc[n][4 * q], acc[n][4 * q + 1], acc[n][4 * q + 2], acc[n][4 * q + 3]};
+            Psi[((dblk * C::NB + eblk0 + n) * 4 + q) * 64 + lane] = x;
         }
     if (tid == 0) gam[0] = sc_gam[0];
 }
@@ -276,7 +350,8 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
 {
     constexpr int KS = D / 16;                           // k-steps of the D-long contraction
     constexpr int SROW = 2 * D + 16;                     // LDS bytes per state column (conflict-free b128 reads)
-    constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row]
+    constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row slot]
+    constexpr int PFD = GDN_PFD, NBUF = PFD + 1;
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * SBUF];   // [buffer][hi, lo]
 
     const int tid = threadIdx.x;
@@ -291,66 +366,80 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
     for (int r = 0; r < 16; ++r) s_acc[r] = Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D];
 
     const unsigned char *ws = (const unsigned char *)a.workspace + (size_t)bh * nblk * gdn_block_bytes(D);
-    bf16x8 ehi[2][KS], elo[2][KS];
-    float psi[2][16], gam[2];
-    auto fetch = [&](int blk, int buf) {                 // this wavefront's rows of -E, its block of Psi
+    // operands of the next PFD blocks are kept in flight (registers), a ring of NBUF = PFD + 1 buffers
+    bf16x8 ehi[NBUF][KS], elo[NBUF][KS];
+    f32x4 psi[NBUF][4];
+    float gam[NBUF];
+    // Loads of one block's operands, in KS + 1 parts so that they can be issued between the MFMAs of a
+    // step: the workgroup's loads of a step (80 KB at D = 128) keep the CU's 64-byte-per-clock load path
+    // busy about as long as the step's MFMAs take.
+    auto fetch_part = [&](int blk, auto buf_, auto part_) {
+        constexpr int buf = decltype(buf_)::value, part = decltype(part_)::value;
         const unsigned char *p = ws + (size_t)blk * gdn_block_bytes(D);
-        const bf16_t *Ehi = (const bf16_t *)p + (size_t)(32 * wave + c32) * D + 8 * hh;
+        if constexpr (part < KS) {                       // this wavefront's rows of -E, fragment order [row block][k-step][lane]
+            const bf16x8 *Ehi = (const bf16x8 *)p + wave * KS * 64 + lane;
+            ehi[buf][part] = Ehi[part * 64];
+            elo[buf][part] = Ehi[D * D / 8 + part * 64];
+        } else {                                         // its block of Psi, accumulator order
+            const f32x4 *Psi = (const f32x4 *)(p + (size_t)D * D * 4) + (wave * (D / 32) + slice) * 4 * 64 + lane;
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            ehi[buf][t] = *(const bf16x8 *)(Ehi + 16 * t);
-            elo[buf][t] = *(const bf16x8 *)(Ehi + D * D + 16 * t);
+            for (int q = 0; q < 4; ++q) psi[buf][q] = Psi[q * 64];
+            gam[buf] = *(const float *)(p + (size_t)D * D * 8);
         }
-        const float *Psi = (const float *)(p + (size_t)D * D * 4) + 32 * slice + c32;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) psi[buf][r] = Psi[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D];
-        gam[buf] = *(const float *)(p + (size_t)D * D * 8);
     };
-    auto step = [&](int blk, int buf) {
-        if (blk + 1 < nblk) fetch(blk + 1, buf ^ 1);
-        // publish this wavefront's 32 rows of the slice as bf16 hi + lo, [column][row]
+    auto fetch = [&](int blk, auto buf_) {
+        static_for<0, KS + 1>([&](auto part_) { fetch_part(blk, buf_, part_); });
+    };
+    // The slice is published [column][slot] with the rows of each 16-row group in k-slot order: slot
+    // 8 hh + j holds row 16 t + 8 (j / 4) + 4 hh + j % 4, so that one 16-byte read is a B operand that
+    // matches the stored A fragments of -E.  This lane's register quads 2 p, 2 p + 1 are slots 0..7 of
+    // its half of group 2 wave + p.
+    const int st_w = c32 * SROW + 2 * (32 * wave + 8 * hh);
+    const int st_r = c32 * SROW + 16 * hh;
+    auto step = [&](int blk, auto buf_) {
+        constexpr int buf = decltype(buf_)::value;
+        // past the last block this re-reads the last one (unused), which keeps the loop free of branches
+        const int nxt = blk + PFD < nblk ? blk + PFD : nblk - 1;
+        const std::integral_constant<int, (buf + PFD) % NBUF> nbuf{};
+        fetch_part(nxt, nbuf, std::integral_constant<int, KS>{});
         unsigned char *sb = smem + (blk & 1) * 2 * SBUF;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bf16x4 h4, l4;
+        for (int p = 0; p < 2; ++p) {
+            bf16x8 h8, l8;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float x = s_acc[4 * q + i];
-                h4[i] = to_bf16(x);
-                l4[i] = to_bf16(x - (float)h4[i]);
+            for (int e = 0; e < 8; ++e) {
+                const float x = s_acc[8 * p + e];
+                h8[e] = to_bf16(x);
+                l8[e] = to_bf16(x - (float)h8[e]);
             }
-            const int off = c32 * SROW + 2 * (row0 + 8 * q);
-            *(bf16x4 *)(sb + off) = h4;
-            *(bf16x4 *)(sb + SBUF + off) = l4;
+            *(bf16x8 *)(sb + st_w + 32 * p) = h8;
+            *(bf16x8 *)(sb + SBUF + st_w + 32 * p) = l8;
         }
         __syncthreads();
-        f32x16 acc0, acc1, acc2;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            acc0[r] = fmaf(gam[buf], s_acc[r], psi[buf][r]);
-            acc1[r] = 0.f;
-            acc2[r] = 0.f;
-        }
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const bf16x8 sh = *(const bf16x8 *)(sb + c32 * SROW + 32 * t + 16 * hh);
-            const bf16x8 sl = *(const bf16x8 *)(sb + SBUF + c32 * SROW + 32 * t + 16 * hh);
+        f32x16 acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc1 = acc0, acc2 = acc0;
+        static_for<0, KS>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            const bf16x8 sh = *(const bf16x8 *)(sb + st_r + 32 * t);
+            const bf16x8 sl = *(const bf16x8 *)(sb + SBUF + st_r + 32 * t);
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi[buf][t], sh, acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi[buf][t], sl, acc1, 0, 0, 0);
             acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo[buf][t], sh, acc2, 0, 0, 0);
-        }
+            fetch_part(nxt, nbuf, t_);
+            __builtin_amdgcn_sched_barrier(0);
+        });
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_acc[r] = acc0[r] + (acc1[r] + acc2[r]);
+        for (int r = 0; r < 16; ++r)
+            s_acc[r] = (fmaf(gam[buf], s_acc[r], psi[buf][r >> 2][r & 3]) + acc0[r]) + (acc1[r] + acc2[r]);
     };
 
-    fetch(0, 0);
+    static_for<0, PFD>([&](auto i_) { fetch(decltype(i_)::value < nblk ? decltype(i_)::value : nblk - 1, i_); });
     int blk = 0;
 #pragma unroll 1
-    for (; blk + 1 < nblk; blk += 2) {
-        step(blk, 0);
-        step(blk + 1, 1);
-    }
-    if (blk < nblk) step(blk, 0);
+    for (; blk + NBUF <= nblk; blk += NBUF)
+        static_for<0, NBUF>([&](auto i_) { step(blk + decltype(i_)::value, i_); });
+    static_for<0, NBUF - 1>([&](auto i_) {
+        if (blk + decltype(i_)::value < nblk) step(blk + decltype(i_)::value, i_);
+    });
 
 #pragma unroll
     for (int r = 0; r < 16; ++r) Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D] = s_acc[r];
