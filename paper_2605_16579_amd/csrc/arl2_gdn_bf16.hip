@@ -225,22 +225,94 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
     }
     __syncthreads();
 
-    // ---- 4. back substitution (I + A)^T Z = diag(tail r) K, thread = feature; row i of A updates rows j < i
+    // ---- 4. back substitution (I + A)^T Z = diag(tail r) K in blocks of 16 tokens, last block first.
+    // The 16 x 16 diagonal systems are solved on the vector ALU, thread = feature (row i of A updates
+    // rows j < i, all independent).  What a solved block contributes to the rows before it,
+    // U[j][f] = sum_{i in block} A_ij Z_i[f], is one MFMA k-step: A from the fp32 matrix in LDS and the
+    // block of Z passed through LDS, both split into bf16 hi + lo (three terms); U stays in accumulators
+    // (wavefront = 32 features, rows 0..63 as two 32-row blocks) and only the 16 rows the next block
+    // needs travel back through LDS.
     float z[CT];
-    if (tid < D) {
+    {
         const float *As = (const float *)R2;
+        unsigned char *Zb = R3;                                   // [feature][16 tokens] bf16, hi then lo
+        float *Ux = (float *)(R3 + 2 * D * 32);                   // [16 rows][D + 4] fp32
+        constexpr int UST = D + 4;
+        if (tid < D) {
 #pragma unroll
-        for (int i = 0; i < CT; ++i) z[i] = sc_tr[i] * (float)*(const bf16_t *)(R0 + i * C::ROW + 2 * tid);
-        static_for<0, CT - 1>([&](auto ii_) {
-            constexpr int i = CT - 1 - decltype(ii_)::value;       // z[i] is final; i = 63 .. 1
-            static_for<0, (i + 3) / 4>([&](auto q_) {
-                constexpr int q = decltype(q_)::value;
-                const f32x4 a4 = *(const f32x4 *)(As + i * C::AST + 4 * q);
-                static_for<0, 4>([&](auto e_) {
-                    constexpr int j = 4 * q + decltype(e_)::value;
-                    if constexpr (j < i) z[j] = fmaf(-a4[j - 4 * q], z[i], z[j]);
+            for (int i = 0; i < CT; ++i) z[i] = sc_tr[i] * (float)*(const bf16_t *)(R0 + i * C::ROW + 2 * tid);
+        }
+        f32x16 U[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) U[rb][r] = 0.f;
+        static_for<0, 4>([&](auto bb_) {
+            constexpr int b4 = 3 - decltype(bb_)::value, i0 = 16 * b4;          // token block 3, 2, 1, 0
+            if (tid < D) {
+                // the block's 120 entries of A first, so that their LDS latency is paid once
+                f32x4 a4[15][4];
+                static_for<1, 16>([&](auto il_) {
+                    constexpr int il = decltype(il_)::value;
+                    static_for<0, (il + 3) / 4>([&](auto q_) {
+                        constexpr int q = decltype(q_)::value;
+                        a4[il - 1][q] = *(const f32x4 *)(As + (i0 + il) * C::AST + i0 + 4 * q);
+                    });
                 });
-            });
+                if constexpr (b4 < 3) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) z[i0 + e] -= Ux[e * UST + tid];
+                }
+                static_for<0, 15>([&](auto ii_) {
+                    constexpr int il = 15 - decltype(ii_)::value;                  // z[i0 + il] is final
+                    static_for<0, il>([&](auto jl_) {
+                        constexpr int jl = decltype(jl_)::value;
+                        z[i0 + jl] = fmaf(-a4[il - 1][jl / 4][jl % 4], z[i0 + il], z[i0 + jl]);
+                    });
+                });
+                if constexpr (b4 > 0) {
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        bf16x8 h8, l8;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float x = z[i0 + 8 * half + e];
+                            h8[e] = to_bf16(x);
+                            l8[e] = to_bf16(x - (float)h8[e]);
+                        }
+                        *(bf16x8 *)(Zb + tid * 32 + 16 * half) = h8;
+                        *(bf16x8 *)(Zb + D * 32 + tid * 32 + 16 * half) = l8;
+                    }
+                }
+            }
+            if constexpr (b4 > 0) {
+                __syncthreads();
+                if (wave < C::NB) {
+                    const bf16x8 zh = *(const bf16x8 *)(Zb + (32 * wave + c32) * 32 + 16 * hh);
+                    const bf16x8 zl = *(const bf16x8 *)(Zb + D * 32 + (32 * wave + c32) * 32 + 16 * hh);
+                    constexpr int NRB = (i0 + 31) / 32;                                 // 32-row blocks that hold rows < i0
+                    static_for<0, NRB>([&](auto rb_) {
+                        constexpr int rb = decltype(rb_)::value;
+                        const int j = 32 * rb + c32;
+                        bf16x8 ah, al;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float x = j < i0 ? As[(i0 + 8 * hh + e) * C::AST + j] : 0.f;
+                            ah[e] = to_bf16(x);
+                            al[e] = to_bf16(x - (float)ah[e]);
+                        }
+                        U[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, zh, U[rb], 0, 0, 0);
+                        U[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, zl, U[rb], 0, 0, 0);
+                        U[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, zh, U[rb], 0, 0, 0);
+                    });
+                    // rows i0 - 16 .. i0 - 1 of U go to the feature threads
+                    constexpr int rb = (i0 - 16) / 32, r0 = ((i0 - 16) % 32) / 8 * 4;  // 32-row block, first register
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        Ux[(8 * (r >> 2) + 4 * hh + (r & 3)) * UST + 32 * wave + c32] = U[rb][r0 + r];
+                }
+                __syncthreads();
+            }
         });
     }
     __syncthreads();                                     // A is dead: R2, R3 become the Z^T tiles
@@ -352,6 +424,7 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
     constexpr int SROW = 2 * D + 16;                     // LDS bytes per state column (conflict-free b128 reads)
     constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row slot]
     constexpr int PFD = GDN_PFD, NBUF = PFD + 1;
+    constexpr int EARLY = 2;                             // k-steps whose loads are issued before the MFMAs start
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * SBUF];   // [buffer][hi, lo]
 
     const int tid = threadIdx.x;
@@ -402,6 +475,7 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
         const int nxt = blk + PFD < nblk ? blk + PFD : nblk - 1;
         const std::integral_constant<int, (buf + PFD) % NBUF> nbuf{};
         fetch_part(nxt, nbuf, std::integral_constant<int, KS>{});
+        static_for<0, EARLY>([&](auto part_) { fetch_part(nxt, nbuf, part_); });
         unsigned char *sb = smem + (blk & 1) * 2 * SBUF;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -424,7 +498,7 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi[buf][t], sh, acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ehi[buf][t], sl, acc1, 0, 0, 0);
             acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(elo[buf][t], sh, acc2, 0, 0, 0);
-            fetch_part(nxt, nbuf, t_);
+            if constexpr (t + EARLY < KS) fetch_part(nxt, nbuf, std::integral_constant<int, t + EARLY>{});
             __builtin_amdgcn_sched_barrier(0);
         });
 #pragma unroll

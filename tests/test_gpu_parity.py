@@ -367,6 +367,26 @@ def test_gdn_commit_small(lib, oracle, D, L):
         assert e <= TOL_STATE, f"D={D} L={L} update {c}: {e:.3e}"
 
 
+@pytest.mark.parametrize("D,L", [(128, 1700), (128, 3141), (64, 1700)])
+def test_gdn_commit_long_chunks(lib, oracle, D, L):
+    """Chunks long enough that the per-block maps are composed pairwise (one and two levels, with an
+    odd block left over at a level) before the in-order scan."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gdn_long{D}", B=1, H=2, D=D, L=L)
+    S0 = W.normal(5, w, (w.B, w.H, w.D, w.D), 0, 0, 92, io_dtype="f32")
+    S_ref = to_np(S0).astype(np.float64)
+    S_dev = dev(S0).clone()
+    ws = _gdn_ws(lib, w)
+    for c in range(2):
+        k, v, _ = W.clean_inputs(w, c)
+        alpha, beta = W.token_gates(w, c)
+        S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+        lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(S_dev), S_ref)
+        assert e <= TOL_STATE, f"D={D} L={L} update {c}: {e:.3e}"
+
+
 def test_gdn_commit_gate_edge_values(lib, oracle):
     """Gates of exactly 0 and 1 and learning rates of exactly 0 and 1 inside and across blocks."""
     import dataclasses
