@@ -38,11 +38,13 @@ def fwd_bytes(B, H, L, D, io_bytes):
     return B * (4.0 * L * H * D * io_bytes + H * D * D * 4.0 + L * H * 4.0)
 
 
-def commit_bytes(B, H, L, D, io_bytes):
-    return B * (2.0 * L * H * D * io_bytes + 2.0 * H * D * D * 4.0)
+def commit_bytes(B, H, L, D, io_bytes, rule="plain"):
+    """Algorithmic bytes of one commit: k and v read once, S read and written, per-token gates if any."""
+    gates = 2.0 * L * H * 4.0 if rule == "gdn" else 0.0
+    return B * (2.0 * L * H * D * io_bytes + 2.0 * H * D * D * 4.0 + gates)
 
 
-def cpu_baseline(w, passes_inputs, clean, S0, steps):
+def cpu_baseline(w, passes_inputs, clean, S0, steps, rule="plain", rule_inputs=None):
     """The oracle as it stands (fp64, OpenMP over independent rows), timed on this machine's host cores
     on whole chunk steps of the same workload: every readout pass in full, then the commit."""
     import numpy as np
@@ -59,7 +61,12 @@ def cpu_baseline(w, passes_inputs, clean, S0, steps):
     for _ in range(steps):
         for (q, k, v, g) in ins:
             O.fwd(q, k, v, S64, g)
-        S64 = O.commit(kc, vc, gate, S64)
+        if rule == "plain":
+            S64 = O.commit(kc, vc, gate, S64)
+        elif rule == "delta":
+            S64 = O.commit_delta(kc, vc, gate, f(rule_inputs[0]), S64)
+        else:
+            S64 = O.commit_gdn(kc, vc, f(rule_inputs[0]), f(rule_inputs[1]), S64)
     t_step = (time.perf_counter() - t0) / steps
     return {
         "value": w.B * w.L / t_step, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
@@ -82,6 +89,22 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
     out = torch.empty_like(q)
     S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
     ws = A.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype, device=dev)
+    rule = args.commit_rule
+    rule_cpu = None
+    if rule == "delta":       # learning rate in the range where the frame-level rule is a contraction (below 2 D / L)
+        rule_cpu = (W.uniform(0, w, (w.B, w.H), 0.2 * w.D / w.L, 1.0 * w.D / w.L, 0, 0, 77),)
+    elif rule == "gdn":
+        rule_cpu = W.token_gates(w, 0)
+        ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
+    rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
+
+    def commit():
+        if rule == "plain":
+            A.arl2_state_commit(kc, vc, gate, S, ws)
+        elif rule == "delta":
+            A.arl2_state_commit_delta(kc, vc, gate, rule_dev[0], S, ws)
+        else:
+            A.arl2_state_commit_gdn(kc, vc, rule_dev[0], rule_dev[1], S, ws_gdn)
     A.arl2_state_commit(kc, vc, gate, S, ws)
     kv_k = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 101).to(dev)
     kv_v = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 102).to(dev)
@@ -129,6 +152,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
+    ap.add_argument("--commit-rule", default="plain", choices=["plain", "delta", "gdn"],
+                    help="state update of the step: plain (the headline: gate * S + K'^T V), delta (Eq. (4) at frame "
+                         "level, one learning rate per head), gdn (Eq. (4) token by token, per-token gates)")
     ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stack-report", action="store_true",
@@ -177,6 +203,22 @@ def main() -> int:
     outs = [torch.empty_like(passes[p][0]) for p in range(w.passes)]
     S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
     ws = A.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype, device=dev)
+    rule = args.commit_rule
+    rule_cpu = None
+    if rule == "delta":       # learning rate in the range where the frame-level rule is a contraction (below 2 D / L)
+        rule_cpu = (W.uniform(0, w, (w.B, w.H), 0.2 * w.D / w.L, 1.0 * w.D / w.L, 0, 0, 77),)
+    elif rule == "gdn":
+        rule_cpu = W.token_gates(w, 0)
+        ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
+    rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
+
+    def commit():
+        if rule == "plain":
+            A.arl2_state_commit(kc, vc, gate, S, ws)
+        elif rule == "delta":
+            A.arl2_state_commit_delta(kc, vc, gate, rule_dev[0], S, ws)
+        else:
+            A.arl2_state_commit_gdn(kc, vc, rule_dev[0], rule_dev[1], S, ws_gdn)
     for j in range(w.prefill):     # input preparation: the state the chunk starts from
         pk, pv, pg = (t.to(dev) for t in W.prefill_inputs(w, j))
         A.arl2_state_commit(pk, pv, pg, S, ws)
@@ -196,7 +238,7 @@ def main() -> int:
             e1 = torch.cuda.Event(enable_timing=True)
             e1.record()
             events.append((e0, e1))
-        A.arl2_state_commit(kc, vc, gate, S, ws)
+        commit()
 
     for _ in range(args.warmup):
         step()
@@ -231,14 +273,14 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
+                   "passes": w.passes, "commit_rule": rule, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,
         "token_passes_per_s": w.B * w.L * w.passes / (ms_per_step * 1e-3),
         "fwd_ms": fwd_avg_ms, "fwd_ms_min": min(fwd_ms),
         "commit_ms": com_avg_ms, "commit_ms_min": min(com_ms),
-        "commit_gbs": commit_bytes(w.B, w.H, w.L, w.D, io_bytes) / (com_avg_ms * 1e-3) / 1e9,
-        "commit_frac_hbm_peak": commit_bytes(w.B, w.H, w.L, w.D, io_bytes) / (com_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "commit_gbs": commit_bytes(w.B, w.H, w.L, w.D, io_bytes, rule) / (com_avg_ms * 1e-3) / 1e9,
+        "commit_frac_hbm_peak": commit_bytes(w.B, w.H, w.L, w.D, io_bytes, rule) / (com_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "fwd_gbs": fwd_bytes(w.B, w.H, w.L, w.D, io_bytes) / (fwd_avg_ms * 1e-3) / 1e9,
         "roofline": {"kernel": "fwd_bf16_kernel (flash softmax + fused state readout)",
                      "bound": "mfma", "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -250,7 +292,7 @@ def main() -> int:
         if t:
             result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps)
+        result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps, rule, rule_cpu)
     print(json.dumps(result), flush=True)
     return 0
 

@@ -35,7 +35,10 @@ namespace {
 constexpr int CT = 64;     // tokens per block
 constexpr int NTA = 256;   // threads of the block kernel
 #ifndef GDN_PFD
-#define GDN_PFD 2
+#define GDN_PFD 2        // blocks whose operands the scan keeps in flight
+#endif
+#ifndef GDN_EARLY
+#define GDN_EARLY 2      // k-steps of the next operands that the scan requests before its MFMAs start
 #endif
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
@@ -424,13 +427,17 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
     constexpr int SROW = 2 * D + 16;                     // LDS bytes per state column (conflict-free b128 reads)
     constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row slot]
     constexpr int PFD = GDN_PFD, NBUF = PFD + 1;
-    constexpr int EARLY = 2;                             // k-steps whose loads are issued before the MFMAs start
+    constexpr int EARLY = GDN_EARLY;                             // k-steps whose loads are issued before the MFMAs start
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * SBUF];   // [buffer][hi, lo]
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
-    const int slice = blockIdx.x % (D / 32);
-    const int bh = blockIdx.x / (D / 32);
+    // The column slices of one head read the same -E: all of them run on one XCD (consecutive workgroup
+    // ids go round the 8 XCDs), so that its L2 serves the re-reads.  The grid is padded to whole heads per XCD.
+    const int xcd = blockIdx.x % kNumXcd, loc = blockIdx.x / kNumXcd;
+    const int slice = loc % (D / 32);
+    const int bh = (loc / (D / 32)) * kNumXcd + xcd;
+    if (bh >= a.B * a.H) return;
     float *Sg = a.S + (size_t)bh * D * D + 32 * slice + c32;
     const int row0 = 32 * wave + 4 * hh;                 // accumulator register r holds row row0 + 8 (r / 4) + r % 4
 
@@ -533,7 +540,8 @@ hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream)
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
     // the block kernel addresses one stream's K (or V) with 32-bit byte offsets
     if ((long long)(a.L + 4 * CT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
-    const unsigned nscan = (unsigned)(a.B * a.H * (a.D / 32));
+    // whole heads per XCD: ceil(B H / 8) heads on each of the 8 XCDs, D / 32 workgroups per head
+    const unsigned nscan = (unsigned)(((a.B * a.H + kNumXcd - 1) / kNumXcd) * kNumXcd * (a.D / 32));
     if (a.D == 128) {
         hipLaunchKernelGGL(gdn_block_kernel<128>, dim3((unsigned)nwg), dim3(NTA), 0, stream, a, nblk);
         hipError_t e = hipGetLastError();
