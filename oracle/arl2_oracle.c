@@ -45,6 +45,8 @@
 /* One query row i of one (b,h): Eq. (2) + Eq. (3) + Eq. (5) + Eq. (6). */
 static void fwd_row_f64(int H, int Lkv, int D,
                         const float *q_row,            /* q[b][i][h][:]              */
+                        const float *ql_row,           /* row the inter branch normalises: q_row, or
+                                                          RoPE(phi_q(Q)) of Eq. (3) when given apart */
                         const float *k_bh,             /* k[b][0][h][:], stride H*D  */
                         const float *v_bh,             /* v[b][0][h][:], stride H*D  */
                         const double *S_bh,            /* S[b][h] or NULL            */
@@ -82,12 +84,12 @@ static void fwd_row_f64(int H, int Lkv, int D,
     if (S_bh) {
         double n2 = 0.0;
         for (int d = 0; d < D; ++d)
-            n2 += (double)q_row[d] * (double)q_row[d];
+            n2 += (double)ql_row[d] * (double)ql_row[d];
         const double nq = sqrt(n2 + l2_eps);
         for (int e = 0; e < D; ++e) {
             double o = 0.0;
             for (int d = 0; d < D; ++d)
-                o += ((double)q_row[d] / nq) * S_bh[(size_t)d * D + e];
+                o += ((double)ql_row[d] / nq) * S_bh[(size_t)d * D + e];
             out_row[e] += g_i * o;
         }
     }
@@ -99,12 +101,34 @@ static void fwd_row_f64(int H, int Lkv, int D,
  * S == NULL: zero state (pure softmax).  g == NULL: gate of one.
  * Returns 0, or -1 on allocation failure.
  */
+int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
+                     const float *q, const float *k, const float *v, const float *q_lin,
+                     const double *S, const float *g,
+                     double sm_scale, double l2_eps,
+                     const int32_t *rows, int nrows,
+                     double *out);
+
 int arl2o_fwd_f64(int B, int H, int Lq, int Lkv, int D,
                   const float *q, const float *k, const float *v,
                   const double *S, const float *g,
                   double sm_scale, double l2_eps,
                   const int32_t *rows, int nrows,
                   double *out)
+{
+    return arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, q, k, v, NULL, S, g, sm_scale, l2_eps, rows, nrows, out);
+}
+
+/*
+ * The same pass with the inter branch's query given apart: q_lin [B][Lq][H][D] holds RoPE(phi_q(Q))
+ * of Eq. (3), which the inter branch normalises and multiplies with S (Eq. (5)), while the intra
+ * branch keeps q (Eq. (2)).  q_lin == NULL: the inter branch normalises q itself.
+ */
+int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
+                     const float *q, const float *k, const float *v, const float *q_lin,
+                     const double *S, const float *g,
+                     double sm_scale, double l2_eps,
+                     const int32_t *rows, int nrows,
+                     double *out)
 {
     int fail = 0;
     const long total = (long)B * H * nrows;
@@ -129,7 +153,8 @@ int arl2o_fwd_f64(int B, int H, int Lq, int Lkv, int D,
                 const double *S_bh = S ? S + ((size_t)b * H + h) * D * D : NULL;
                 const double g_i = g ? (double)g[((size_t)b * Lq + i) * H + h] : 1.0;
                 double *out_row = out + (((size_t)b * nrows + r) * H + h) * D;
-                fwd_row_f64(H, Lkv, D, q_row, k_bh, v_bh, S_bh, g_i, sm_scale, l2_eps,
+                const float *ql_row = q_lin ? q_lin + (((size_t)b * Lq + i) * H + h) * D : q_row;
+                fwd_row_f64(H, Lkv, D, q_row, ql_row, k_bh, v_bh, S_bh, g_i, sm_scale, l2_eps,
                             score, out_row);
             }
         }
@@ -289,6 +314,46 @@ int arl2o_commit_gdn_f64(int B, int H, int L, int D,
         }
     }
     return fail ? -1 : 0;
+}
+
+/*
+ * Per-head feature map of Eq. (3) without its L2Norm (the readout and the commits normalise):
+ *     y[b][l][h][:] = RoPE_l( W[h] x[b][l][h][:] )
+ * W [H][D][D] holds, per head, the D x D matrix of the grouped 1 x 1 map, indexed [out][in].
+ * RoPE rotates the pairs (y[2i], y[2i+1]) by the angle whose cosine and sine are cs[l][i], sn[l][i]
+ * ([L][D/2]; which positions and frequencies they encode is the caller's choice).  cs == NULL: no
+ * rotation (the value map phi_v).
+ */
+int arl2o_feature_map_f64(int B, int H, int L, int D,
+                          const float *x, const float *W,
+                          const double *cs, const double *sn,
+                          double *y)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b) {
+        for (int l = 0; l < L; ++l) {
+            for (int h = 0; h < H; ++h) {
+                const float *x_row = x + (((size_t)b * L + l) * H + h) * D;
+                double *y_row = y + (((size_t)b * L + l) * H + h) * D;
+                const float *W_h = W + (size_t)h * D * D;
+                for (int e = 0; e < D; ++e) {
+                    double acc = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        acc += (double)W_h[(size_t)e * D + d] * (double)x_row[d];
+                    y_row[e] = acc;
+                }
+                if (cs) {
+                    for (int i = 0; i < D / 2; ++i) {
+                        const double c = cs[(size_t)l * (D / 2) + i], s_ = sn[(size_t)l * (D / 2) + i];
+                        const double y0 = y_row[2 * i], y1 = y_row[2 * i + 1];
+                        y_row[2 * i] = y0 * c - y1 * s_;
+                        y_row[2 * i + 1] = y0 * s_ + y1 * c;
+                    }
+                }
+            }
+        }
+    }
+    return 0;
 }
 
 /* ---------------------------------------------------------------- fp32 -- */

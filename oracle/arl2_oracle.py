@@ -52,6 +52,10 @@ def _load():
         lib.arl2o_commit_f32.restype = i32
         lib.arl2o_commit_delta_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
         lib.arl2o_commit_delta_f64.restype = i32
+        lib.arl2o_fwd_ex_f64.argtypes = [i32] * 5 + [vp] * 6 + [f64, f64, vp, i32, vp]
+        lib.arl2o_fwd_ex_f64.restype = i32
+        lib.arl2o_feature_map_f64.argtypes = [i32] * 4 + [vp] * 5
+        lib.arl2o_feature_map_f64.restype = i32
         lib.arl2o_commit_gdn_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
         lib.arl2o_commit_gdn_f64.restype = i32
         lib.arl2o_num_threads.restype = i32
@@ -86,8 +90,11 @@ def _check_shapes(q, k, v, S, g):
 
 
 def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: float = L2_EPS,
-        rows: Optional[Sequence[int]] = None, precision: str = "f64") -> np.ndarray:
+        rows: Optional[Sequence[int]] = None, precision: str = "f64", q_lin=None) -> np.ndarray:
     """Readout pass: out = softmax(q k^T * sm_scale) v + g * L2Norm(q) S   (Eq. 2, 3, 5, 6).
+
+    ``q_lin`` (fp64 path only), if given, is the row the inter branch normalises instead of q:
+    RoPE(phi_q(Q)) of Eq. (3).
 
     ``rows`` restricts the computation to those query indices (each output row
     depends only on its own q row and on all of k, v, S); the result is then
@@ -109,6 +116,17 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
         if nrows and (rows_arr.min() < 0 or rows_arr.max() >= Lq):
             raise ValueError("row index out of range")
     out = np.empty((B, nrows, H, D), dtype=st)
+    if q_lin is not None:
+        if precision != "f64":
+            raise ValueError("q_lin is supported by the fp64 oracle only")
+        q_lin = _c(q_lin, np.float32)
+        if q_lin.shape != q.shape:
+            raise ValueError("q_lin must have the shape of q")
+        rc = lib.arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, _ptr(q), _ptr(k), _ptr(v), _ptr(q_lin), _ptr(S), _ptr(g),
+                                  float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
+        if rc != 0:
+            raise MemoryError("oracle fwd failed")
+        return out
     fn = lib.arl2o_fwd_f64 if precision == "f64" else lib.arl2o_fwd_f32
     rc = fn(B, H, Lq, Lkv, D, _ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(g),
             float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
@@ -171,6 +189,29 @@ def commit_gdn(k, v, alpha, beta, S, *, l2_eps: float = L2_EPS) -> np.ndarray:
     if rc != 0:
         raise MemoryError("oracle commit_gdn failed")
     return S_new
+
+
+def feature_map(x, W, cos=None, sin=None) -> np.ndarray:
+    """Per-head feature map of Eq. (3) without the L2Norm: RoPE(W[h] x) per (token, head), fp64.
+    x [B, L, H, D]; W [H, D, D] indexed [head, out, in]; cos, sin [L, D/2] (None: no rotation)."""
+    lib = _load()
+    x, W = _c(x, np.float32), _c(W, np.float32)
+    if x.ndim != 4:
+        raise ValueError("x must be [B, L, H, D]")
+    B, L, H, D = x.shape
+    if W.shape != (H, D, D) or D % 2:
+        raise ValueError("W must be [H, D, D] and D even")
+    if (cos is None) != (sin is None):
+        raise ValueError("give both cos and sin or neither")
+    if cos is not None:
+        cos, sin = _c(cos, np.float64), _c(sin, np.float64)
+        if cos.shape != (L, D // 2) or sin.shape != (L, D // 2):
+            raise ValueError("cos, sin must be [L, D/2]")
+    y = np.empty((B, L, H, D), dtype=np.float64)
+    rc = lib.arl2o_feature_map_f64(B, H, L, D, _ptr(x), _ptr(W), _ptr(cos), _ptr(sin), _ptr(y))
+    if rc != 0:
+        raise MemoryError("oracle feature_map failed")
+    return y
 
 
 def rollout(chunks, S0=None, *, l2_eps: float = L2_EPS, precision: str = "f64", rows=None):

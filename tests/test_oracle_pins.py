@@ -474,3 +474,63 @@ def test_gdn_commit_splits_into_consecutive_calls(oracle):
     m = 8
     half = oracle.commit_gdn(k[:, :m], v[:, :m], alpha[:, :m], beta[:, :m], S)
     np.testing.assert_allclose(oracle.commit_gdn(k[:, m:], v[:, m:], alpha[:, m:], beta[:, m:], half), whole, rtol=1e-13, atol=1e-14)
+
+
+# ---------------------------------------------------------------- feature maps of Eq. (3) and the inter branch's own query
+
+def test_feature_map_hand_example_and_identity(oracle):
+    # D = 2: W x = (1*1 + 2*1, 3*1 + 4*1) = (3, 7); a quarter turn maps (3, 7) to (-7, 3)
+    x = np.array([1.0, 1.0], dtype=np.float32).reshape(1, 1, 1, 2)
+    Wm = np.array([[1.0, 2.0], [3.0, 4.0]], dtype=np.float32).reshape(1, 2, 2)
+    np.testing.assert_allclose(oracle.feature_map(x, Wm)[0, 0, 0], [3.0, 7.0], atol=1e-15)
+    y = oracle.feature_map(x, Wm, np.array([[0.0]]), np.array([[1.0]]))
+    np.testing.assert_allclose(y[0, 0, 0], [-7.0, 3.0], atol=1e-15)
+    # identity weights, no rotation: the input comes back
+    xr = rand(2, 5, 3, 8)
+    eye = np.broadcast_to(np.eye(8, dtype=np.float32), (3, 8, 8)).copy()
+    np.testing.assert_array_equal(oracle.feature_map(xr, eye), xr.astype(np.float64))
+
+
+def test_feature_map_matches_einsum_and_complex_rotation(oracle):
+    """W is indexed [head, out, in] (a transposed or head-shared weight fails); the rotation of a pair
+    is multiplication of y0 + i y1 by exp(i theta)."""
+    B, L, H, D = 2, 7, 3, 8
+    x, Wm = rand(B, L, H, D), rand(H, D, D)
+    th = rng.uniform(-3.0, 3.0, (L, D // 2))
+    y = oracle.feature_map(x, Wm, np.cos(th), np.sin(th))
+    lin = np.einsum("hed,blhd->blhe", Wm.astype(np.float64), x.astype(np.float64))
+    z = (lin[..., 0::2] + 1j * lin[..., 1::2]) * np.exp(1j * th)[None, :, None, :]
+    want = np.empty_like(lin)
+    want[..., 0::2], want[..., 1::2] = z.real, z.imag
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-13)
+
+
+def test_rope_depends_on_relative_position_only(oracle):
+    """With theta_i(l) = l * w_i the inner product of two rotated rows is a function of the distance."""
+    L, D = 12, 8
+    w = 1.0 / (100.0 ** (np.arange(D // 2) / (D // 2)))
+    th = np.arange(L)[:, None] * w[None, :]
+    eye = np.eye(D, dtype=np.float32)[None]
+    a, b = rand(D), rand(D)
+    ya = oracle.feature_map(np.broadcast_to(a, (1, L, 1, D)).copy(), eye, np.cos(th), np.sin(th))[0, :, 0]
+    yb = oracle.feature_map(np.broadcast_to(b, (1, L, 1, D)).copy(), eye, np.cos(th), np.sin(th))[0, :, 0]
+    np.testing.assert_allclose(ya[3] @ yb[1], ya[9] @ yb[7], rtol=1e-12)
+    np.testing.assert_allclose(ya[0] @ yb[5], ya[6] @ yb[11], rtol=1e-12)
+    assert abs(ya[3] @ yb[1] - ya[3] @ yb[2]) > 1e-3
+    np.testing.assert_allclose((ya * ya).sum(-1), (a.astype(np.float64) ** 2).sum(), rtol=1e-12)   # a rotation
+
+
+def test_inter_branch_reads_its_own_query(oracle):
+    B, L, H, D = 1, 9, 2, 8
+    q, k, v, ql = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    g = rng.uniform(0.2, 0.8, (B, L, H)).astype(np.float32)
+    eps = oracle.L2_EPS
+    # given q itself, nothing changes; without a state the argument is not read
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, S, g, q_lin=q), oracle.fwd(q, k, v, S, g))
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, None, None, q_lin=ql), oracle.fwd(q, k, v, None, None))
+    # out = intra(q) + g * L2Norm(q_lin) S: the softmax branch never sees q_lin, the linear one never sees q
+    intra = oracle.fwd(q, k, v, None, None)
+    inter = np.einsum("blhd,bhde->blhe", l2n(ql, eps), S) * g[..., None].astype(np.float64)
+    np.testing.assert_allclose(oracle.fwd(q, k, v, S, g, q_lin=ql), intra + inter, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(oracle.fwd(q, k, v, S, g, q_lin=3.0 * ql), intra + inter, rtol=1e-5, atol=1e-5)   # up to eps and the fp32 rounding of 3 q
