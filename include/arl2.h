@@ -20,6 +20,9 @@
  *
  *   arl2_state_commit_gdn  Eq. (4) applied token by token in order, with per-token gates.
  *
+ *   arl2_feature_map       the learned per-head maps and RoPE of Eq. (3) for the linear branch;
+ *   arl2_hybrid_attn_fwd_ex  the readout pass with the linear branch's own query.
+ *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
  * x / sqrt(sum x^2 + l2_eps), and V' = v.
@@ -91,6 +94,34 @@ size_t arl2_workspace_bytes(const arl2_desc *desc);
 arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc,
                                  const void *q, const void *k, const void *v,
                                  const float *S, const void *g, void *out);
+
+/*
+ * The same pass with a query of its own for the linear branch (paper Eq. (3), (5)): the inter branch
+ * normalises and multiplies with S the rows of q_lin, e.g. RoPE(phi_q(Q)) written by arl2_feature_map,
+ * while the softmax branch keeps q (Eq. (2)).
+ *   q_lin     device, io_dtype [B][Lq][H][D]; NULL means q (then this is arl2_hybrid_attn_fwd).
+ *             Not read when S is NULL.
+ */
+arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc,
+                                    const void *q, const void *k, const void *v, const void *q_lin,
+                                    const float *S, const void *g, void *out);
+
+/*
+ * Per-head feature map of the linear branch, paper Eq. (3) without its L2Norm (the readout and the
+ * commits normalise the rows they are given):
+ *     y[b][l][h][:] = RoPE_l( W[h] x[b][l][h][:] )
+ *   x         device bf16 [B][Lq][H][D] (desc->io_dtype must be ARL2_BF16; Lkv is not used).
+ *   W         device bf16 [H][D][D], per head the D x D matrix of the grouped 1 x 1 map, indexed
+ *             [head][out][in].
+ *   rope_cos, rope_sin   device fp32 [Lq][D/2], 8-byte aligned: cosine and sine of the angle by which
+ *             the pair (y[2i], y[2i+1]) of token l is rotated, shared by all streams and heads; which
+ *             positions and frequencies they encode is the caller's choice.  Both NULL: no rotation
+ *             (the value map phi_v).
+ *   y         device bf16 [B][Lq][H][D], fully overwritten; must not alias x or W.
+ * fp32 accumulation and rotation, one rounding to bf16 on output.
+ */
+arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W,
+                             const float *rope_cos, const float *rope_sin, void *y);
 
 /*
  * Post-denoise state update (paper Eq. (3), Eq. (4); Alg. 1 clean pass).

@@ -19,7 +19,8 @@ ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ER
 ARL2_F32, ARL2_BF16 = 0, 1
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
-           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_status_string", "arl2_last_error", "arl2_version"]
+           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_feature_map",
+           "arl2_status_string", "arl2_last_error", "arl2_version"]
 
 
 class arl2_desc(ctypes.Structure):
@@ -57,6 +58,10 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_state_commit.restype = ctypes.c_int
         lib.arl2_state_commit_delta.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_state_commit_delta.restype = ctypes.c_int
+        lib.arl2_hybrid_attn_fwd_ex.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+        lib.arl2_hybrid_attn_fwd_ex.restype = ctypes.c_int
+        lib.arl2_feature_map.argtypes = [dp, vp, vp, vp, vp, vp]
+        lib.arl2_feature_map.restype = ctypes.c_int
         lib.arl2_gdn_workspace_bytes.argtypes = [dp]
         lib.arl2_gdn_workspace_bytes.restype = ctypes.c_size_t
         lib.arl2_state_commit_gdn.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -140,6 +145,41 @@ def arl2_hybrid_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
         _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", (B, Lq, H)),
         _dev(out, "out", (B, Lq, H, D), q.dtype))
+    _check(st)
+
+
+def arl2_hybrid_attn_fwd_ex(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q_lin: Optional[torch.Tensor],
+                            S: Optional[torch.Tensor], g: Optional[torch.Tensor], out: torch.Tensor,
+                            *, sm_scale: float = 0.0, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """The readout pass with the linear branch's own query ``q_lin`` (None: ``q``)."""
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [B, L, H, D]")
+    B, Lq, H, D = q.shape
+    Lkv = k.shape[1]
+    io = _dtype_code(q)
+    d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
+                  stream=stream)
+    st = load_library().arl2_hybrid_attn_fwd_ex(
+        ctypes.byref(d),
+        _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
+        _dev(q_lin, "q_lin", (B, Lq, H, D), q.dtype),
+        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", (B, Lq, H)),
+        _dev(out, "out", (B, Lq, H, D), q.dtype))
+    _check(st)
+
+
+def arl2_feature_map(x: torch.Tensor, W: torch.Tensor, rope_cos: Optional[torch.Tensor],
+                     rope_sin: Optional[torch.Tensor], y: torch.Tensor, *, stream: Optional[int] = None) -> None:
+    """y = RoPE(W[h] x) per (token, head): the feature map of Eq. (3) without its L2Norm.
+    x, y [B, L, H, D] bf16; W [H, D, D] bf16 indexed [head, out, in]; rope_cos, rope_sin [L, D/2] fp32 or None."""
+    if x.dim() != 4:
+        raise ValueError("x must be [B, L, H, D]")
+    B, L, H, D = x.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(x), stream=stream)
+    st = load_library().arl2_feature_map(
+        ctypes.byref(d), _dev(x, "x"), _dev(W, "W", (H, D, D), x.dtype),
+        _dev(rope_cos, "rope_cos", (L, D // 2), torch.float32), _dev(rope_sin, "rope_sin", (L, D // 2), torch.float32),
+        _dev(y, "y", (B, L, H, D), x.dtype))
     _check(st)
 
 

@@ -57,22 +57,24 @@ size_t arl2_workspace_bytes(const arl2_desc *desc)
     return commit_workspace(desc);
 }
 
-arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const void *k, const void *v,
-                                 const float *S, const void *g, void *out)
+arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const void *k, const void *v,
+                                    const void *q_lin, const float *S, const void *g, void *out)
 {
     arl2_status st = check_desc(desc);
     if (st != ARL2_OK) return st;
     if (!q || !k || !v || !out) return fail(ARL2_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(S))
-        return fail(ARL2_ERR_INVALID_ARG, "q, k, v, S and out must be 16-byte aligned");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(S) || !aligned16(q_lin))
+        return fail(ARL2_ERR_INVALID_ARG, "q, k, v, q_lin, S and out must be 16-byte aligned");
     if (g && (reinterpret_cast<uintptr_t>(g) & 3u))
         return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
-    if (out == q || out == k || out == v) return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
+    if (out == q || out == k || out == v || out == q_lin)
+        return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
     if (S != nullptr && desc->Lkv != desc->Lq)
         return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
 
     arl2::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.S = S; a.g = (S != nullptr) ? g : nullptr; a.out = out;
+    a.q_lin = (S != nullptr) ? q_lin : nullptr;
     a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
@@ -81,6 +83,35 @@ arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const voi
     const hipError_t e = desc->io_dtype == ARL2_BF16 ? arl2::launch_fwd_bf16(a, stream)
                                                      : arl2::launch_fwd_f32(a, stream);
     if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "fwd launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
+arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const void *k, const void *v,
+                                 const float *S, const void *g, void *out)
+{
+    return arl2_hybrid_attn_fwd_ex(desc, q, k, v, nullptr, S, g, out);
+}
+
+arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W,
+                             const float *rope_cos, const float *rope_sin, void *y)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!x || !W || !y) return fail(ARL2_ERR_INVALID_ARG, "x, W and y must not be NULL");
+    if (!aligned16(x) || !aligned16(W) || !aligned16(y))
+        return fail(ARL2_ERR_INVALID_ARG, "x, W and y must be 16-byte aligned");
+    if ((rope_cos == nullptr) != (rope_sin == nullptr))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
+    if ((reinterpret_cast<uintptr_t>(rope_cos) & 7u) || (reinterpret_cast<uintptr_t>(rope_sin) & 7u))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be 8-byte aligned");
+    if (y == x || y == W) return fail(ARL2_ERR_INVALID_ARG, "y must not alias an input");
+    if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_feature_map takes bf16 x, W only");
+
+    arl2::FmapArgs a;
+    a.x = x; a.W = W; a.cs = rope_cos; a.sn = rope_sin; a.y = y;
+    a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.D = desc->D;
+    const hipError_t e = arl2::launch_feature_map_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "feature map launch failed: %s", hipGetErrorString(e));
     return ARL2_OK;
 }
 

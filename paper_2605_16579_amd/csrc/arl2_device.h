@@ -25,6 +25,7 @@ constexpr int kWave = 64;
 
 struct FwdArgs {
     const void *q, *k, *v;
+    const void *q_lin;     // row the linear branch normalises; nullptr: q itself
     const float *S;        // may be nullptr
     const void *g;         // may be nullptr
     void *out;
@@ -43,6 +44,14 @@ struct CommitArgs {
     int B, H, L, D;
     int nsplit;            // token splits per (stream, head) for the bf16 path
     float l2_eps;
+};
+
+struct FmapArgs {
+    const void *x;         // [B][L][H][D] bf16
+    const void *W;         // [H][D][D] bf16, indexed [head][out][in]
+    const float *cs, *sn;  // [L][D/2] cosines and sines of the rotation, or both nullptr
+    void *y;               // [B][L][H][D] bf16
+    int B, H, L, D;
 };
 
 struct GdnArgs {
@@ -64,6 +73,7 @@ hipError_t launch_fwd_f32(const FwdArgs &a, hipStream_t stream);
 hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream);
+hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream);
 
 // Workspace of the token-sequential commit (per-block transition maps).
 size_t gdn_workspace_bytes(int B, int H, int L, int D);

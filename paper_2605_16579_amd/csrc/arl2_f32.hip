@@ -69,6 +69,11 @@ __global__ __launch_bounds__(NT) void fwd_f32_kernel(FwdArgs a)
     for (int i = 0; i < EPL; ++i) o[i] /= l;
 
     if (a.S != nullptr) {
+        if (a.q_lin != nullptr) {     // the linear branch's own query (Eq. (3)) replaces q from here on
+            const float *ql = (const float *)a.q_lin + (((size_t)b * Lq + rowc) * H + h) * D + sub * EPL;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) qr[i] = ql[i];
+        }
         float ss = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) ss = fmaf(qr[i], qr[i], ss);

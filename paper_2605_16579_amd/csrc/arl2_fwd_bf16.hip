@@ -339,6 +339,24 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         // (fp32 accumulate), both staged row-major [d][e] in LDS and read as S^T fragments through the
         // transposing LDS read, exactly like V.
         const float *Sg = a.S + ((size_t)b * H + h) * D * D;
+        if (a.q_lin != nullptr) {
+            // the linear branch has a query of its own (Eq. (3): its feature map differs from the
+            // softmax branch's): take its fragments and its squared norm instead
+            const bf16_t *qp = (const bf16_t *)a.q_lin + ((size_t)(b * (size_t)Lq + (qrow < Lq ? qrow : 0)) * H + h) * D + 8 * hh;
+            qss = 0.f;
+#pragma unroll
+            for (int t = 0; t < C::KS; ++t) {
+                bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (qrow < Lq) x = *(const bf16x8 *)(qp + 16 * t);
+                qf[t] = x;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float f = (float)x[j];
+                    qss = fmaf(f, f, qss);
+                }
+            }
+            qss = xhalf_sum(qss);
+        }
         unsigned char *smHi = smem, *smLo = smem + C::SS_BYTES;
         __syncthreads();                              // every wave is done with the K/V ring
 #pragma unroll

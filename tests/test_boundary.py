@@ -112,6 +112,21 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     assert gdn(df) == 2
 
 
+def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
+    lib = A.load_library()
+    d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    fm = lambda d, x=0x1000, W=0x2000, c=0x3000, s=0x4000, y=0x5000: lib.arl2_feature_map(ctypes.byref(d), x, W, c, s, y)
+    assert fm(d, W=None) == 1
+    assert fm(d, c=None) == 1                             # cosines without sines
+    assert fm(d, c=0x3004) == 1                           # tables must be 8-byte aligned
+    assert fm(d, y=0x1000) == 1                           # in place
+    df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
+    assert fm(df) == 2
+    ex = lambda d, ql=0x6000, out=0x5000: lib.arl2_hybrid_attn_fwd_ex(ctypes.byref(d), 0x1000, 0x2000, 0x3000, ql, 0x4000, None, out)
+    assert ex(d, ql=0x6008) == 1                          # misaligned q_lin
+    assert ex(d, ql=0x5000) == 1                          # out aliases q_lin
+
+
 def test_binding_refuses_host_tensors(A):
     import torch
     q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16)

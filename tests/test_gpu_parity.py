@@ -49,8 +49,8 @@ def run_rollout_parity(A, oracle, w, tol_out, tol_state, precision="f64", seed=0
         S_before = S_dev.clone()
         for p in range(w.passes):
             q, k, v, g = W.pass_inputs(w, c, p, seed)
-            # the oracle reads the state the GPU actually holds (fp32), widened exactly
-            ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g))
+            # the oracle reads its own fp64 state chain: nothing the GPU produced ever reaches it
+            ref = oracle.fwd(to_np(q), to_np(k), to_np(v), S_ref, to_np(g))
             got = gpu_fwd(A, q, k, v, S_dev, g)
             e = rel_err(to_np(got), ref)
             worst_out = max(worst_out, e)
@@ -179,9 +179,8 @@ def test_wan_layer_full_size(lib, oracle):
     for p in range(w.passes):
         q, k, v, g = W.pass_inputs(w, 0, p)
         rows = sample_rows(w.L, 256, seed=p)
-        S64 = to_np(S_dev).astype(np.float64)
         got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
-        e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g), rows=rows))
+        e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S_ref, to_np(g), rows=rows))
         # intra branch alone on the same rows
         got_i = to_np(gpu_fwd(lib, q, k, v, None, None))[:, rows]
         ei = rel_err(got_i, oracle.fwd(to_np(q), to_np(k), to_np(v), rows=rows))
@@ -209,7 +208,7 @@ def test_wan_batched_full_size(lib, oracle):
     q, k, v, g = W.pass_inputs(w, 0, 0)
     rows = sample_rows(w.L, 24, seed=7)
     got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
-    e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g), rows=rows))
+    e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S_ref, to_np(g), rows=rows))
     print(f"[wan_batched] out: {e:.3e}", flush=True)
     assert e <= TOL_BF16_OUT
 
@@ -226,7 +225,7 @@ def test_wan_rollout_64_chained_commits(lib, oracle):
             q, k, v, g = W.pass_inputs(w, c, 0)
             rows = sample_rows(w.L, 32, seed=c)
             got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
-            e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S_dev).astype(np.float64), to_np(g), rows=rows))
+            e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S_ref, to_np(g), rows=rows))
             assert e <= TOL_BF16_OUT, f"chunk {c}: out {e:.3e}"
         k, v, gate = W.clean_inputs(w, c)
         S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
@@ -438,3 +437,119 @@ def test_gdn_commit_full_size(lib, oracle):
     lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S2, ws)
     torch.cuda.synchronize()
     assert torch.equal(S_dev, S2)
+
+
+# ---------------------------------------------------------------- feature maps of Eq. (3), the linear branch's own query
+
+def _bf16_round(x64):
+    """What storing an fp64 oracle intermediate in bf16 gives (round to nearest even, once)."""
+    return torch.from_numpy(np.ascontiguousarray(x64, dtype=np.float32)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("D,L,B,H", [(128, 328, 2, 3), (64, 200, 2, 3), (128, 1, 1, 2), (128, 129, 1, 1)])
+def test_feature_map_small(lib, oracle, D, L, B, H):
+    """y = RoPE(W[h] x), element by element; with and without the rotation; ragged tails of the 128-token tile."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"fmap{D}", D=D, L=L, B=B, H=H)
+    x = W.normal(11, w, (w.B, w.L, w.H, w.D), 0, 0, 93)
+    Wq, Wk, Wv = W.feature_weights(w)
+    cs, sn = W.rope_tables(w)
+    y = torch.empty_like(x, device="cuda")
+    for Wm, rope in ((Wq, True), (Wv, False), (Wk, True)):
+        lib.arl2_feature_map(dev(x), dev(Wm), dev(cs) if rope else None, dev(sn) if rope else None, y)
+        torch.cuda.synchronize()
+        ref = oracle.feature_map(to_np(x), to_np(Wm), to_np(cs) if rope else None, to_np(sn) if rope else None)
+        e = rel_err(to_np(y), ref)
+        assert e <= TOL_BF16_OUT, f"D={D} L={L} rope={rope}: {e:.3e}"
+        # one bf16 rounding of an fp32-accurate result: a few ulp at most, element by element
+        assert np.all(np.abs(to_np(y) - ref) <= 2.0 ** -7 * np.abs(ref) + 1e-6 * np.abs(ref).max())
+
+
+def test_identity_feature_map_is_exact_without_rotation(lib):
+    w = W.WORKLOADS["ragged_small"]
+    x = W.normal(12, w, (w.B, w.L, w.H, w.D), 0, 0, 94)
+    eye = torch.eye(w.D, dtype=torch.bfloat16).repeat(w.H, 1, 1).contiguous()
+    y = torch.empty_like(x, device="cuda")
+    lib.arl2_feature_map(dev(x), dev(eye), None, None, y)
+    torch.cuda.synchronize()
+    assert torch.equal(y.cpu(), x)
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_readout_with_own_linear_query(lib, oracle, io):
+    """arl2_hybrid_attn_fwd_ex: the softmax branch sees q, the linear branch q_lin."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="fwd_ex_" + io, io_dtype=io, L=200 if io == "f32" else 328)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    q_lin = W.normal(13, w, (w.B, w.L, w.H, w.D), 0, 0, 95)
+    S = W.normal(14, w, (w.B, w.H, w.D, w.D), 0, 0, 96, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd_ex(dev(q), dev(k), dev(v), dev(q_lin), dev(S), dev(g), out)
+    torch.cuda.synchronize()
+    prec = "f64"
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(g), q_lin=to_np(q_lin), precision=prec)
+    e = rel_err(to_np(out), ref)
+    tol = TOL_BF16_OUT if io == "bf16" else 1e-4
+    assert e <= tol, f"{io}: {e:.3e}"
+    # q_lin = None and q_lin = q are the plain entry point, bit for bit
+    o1, o2, o3 = (torch.empty_like(q, device="cuda") for _ in range(3))
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(g), o1)
+    lib.arl2_hybrid_attn_fwd_ex(dev(q), dev(k), dev(v), None, dev(S), dev(g), o2)
+    lib.arl2_hybrid_attn_fwd_ex(dev(q), dev(k), dev(v), dev(q), dev(S), dev(g), o3)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(o1, o3)
+    # the linear branch does not depend on q: v = 0 leaves g * L2Norm(q_lin) S
+    vz = torch.zeros_like(v)
+    lib.arl2_hybrid_attn_fwd_ex(dev(q), dev(k), dev(vz), dev(q_lin), dev(S), dev(g), o1)
+    lib.arl2_hybrid_attn_fwd_ex(dev(k), dev(k), dev(vz), dev(q_lin), dev(S), dev(g), o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+
+
+def _feature_chain(lib, oracle, w, rows=None):
+    """Eq. (2)-(7) with the feature maps in place, from pre-RoPE projections: one readout pass and one
+    commit on the GPU, and the same chain in the oracle (intermediates rounded to bf16 where the GPU
+    stores bf16; nothing the GPU produced reaches the oracle)."""
+    xq, xk, xv, g = W.pass_inputs(w, 0, 0)
+    xkc, xvc, gate = W.clean_inputs(w, 0)
+    Wq, Wk, Wv = W.feature_weights(w)
+    cs, sn = W.rope_tables(w)
+    eye = torch.eye(w.D, dtype=torch.bfloat16).repeat(w.H, 1, 1).contiguous()
+    S0 = W.normal(15, w, (w.B, w.H, w.D, w.D), 0, 0, 97, io_dtype="f32") * 0.2
+    # ---- GPU
+    d = {n: torch.empty_like(xq, device="cuda") for n in ("q", "k", "ql", "kl", "vl")}
+    lib.arl2_feature_map(dev(xq), dev(eye), dev(cs), dev(sn), d["q"])        # RoPE(Q)           Eq. (2)
+    lib.arl2_feature_map(dev(xk), dev(eye), dev(cs), dev(sn), d["k"])        # RoPE(K)
+    lib.arl2_feature_map(dev(xq), dev(Wq), dev(cs), dev(sn), d["ql"])        # RoPE(phi_q(Q))    Eq. (3)
+    lib.arl2_feature_map(dev(xkc), dev(Wk), dev(cs), dev(sn), d["kl"])       # RoPE(phi_k(K)) of the clean pass
+    lib.arl2_feature_map(dev(xvc), dev(Wv), None, None, d["vl"])             # phi_v(V)
+    S_dev = dev(S0).clone()
+    out = torch.empty_like(xq, device="cuda")
+    lib.arl2_hybrid_attn_fwd_ex(d["q"], d["k"], dev(xv), d["ql"], S_dev, dev(g), out)
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    lib.arl2_state_commit(d["kl"], d["vl"], dev(gate), S_dev, ws)
+    torch.cuda.synchronize()
+    # ---- oracle
+    f = to_np
+    o = {"q": oracle.feature_map(f(xq), f(eye), f(cs), f(sn)), "k": oracle.feature_map(f(xk), f(eye), f(cs), f(sn)),
+         "ql": oracle.feature_map(f(xq), f(Wq), f(cs), f(sn)), "kl": oracle.feature_map(f(xkc), f(Wk), f(cs), f(sn)),
+         "vl": oracle.feature_map(f(xvc), f(Wv))}
+    o = {n: to_np(_bf16_round(x)) for n, x in o.items()}
+    S64 = to_np(S0).astype(np.float64)
+    ref = oracle.fwd(o["q"], o["k"], f(xv), S64, f(g), q_lin=o["ql"], rows=rows)
+    S_ref = oracle.commit(o["kl"], o["vl"], f(gate), S64)
+    got = to_np(out) if rows is None else to_np(out)[:, rows]
+    return rel_err(got, ref), rel_err_per_head(to_np(S_dev), S_ref)
+
+
+def test_feature_map_chain_small(lib, oracle):
+    e_out, e_state = _feature_chain(lib, oracle, W.WORKLOADS["ragged_small"])
+    # a bf16 intermediate of the GPU may fall one ulp from the oracle's: the state tolerance is the bf16 one here
+    assert e_out <= TOL_BF16_OUT and e_state <= 2e-3, f"out {e_out:.3e} state {e_state:.3e}"
+
+
+def test_feature_map_chain_full_size(lib, oracle):
+    w = W.WORKLOADS["wan_layer"]
+    e_out, e_state = _feature_chain(lib, oracle, w, rows=sample_rows(w.L, 64, seed=3))
+    print(f"[wan_layer] feature-map chain: out {e_out:.3e}, state {e_state:.3e}", flush=True)
+    assert e_out <= TOL_BF16_OUT and e_state <= 2e-3

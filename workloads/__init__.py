@@ -82,7 +82,7 @@ def uniform(seed: int, w: Workload, shape, lo: float, hi: float, *ids: int) -> t
 
 
 # tensor tags
-_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE, _TALPHA, _TBETA = range(12)
+_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE, _TALPHA, _TBETA, _WQ, _WK, _WV = range(15)
 
 
 def pass_inputs(w: Workload, chunk: int, p: int, seed: int = 0
@@ -127,6 +127,34 @@ def token_gates(w: Workload, chunk: int, seed: int = 0) -> Tuple[torch.Tensor, t
     alpha = torch.pow(gate, 2.0 * u / w.L).to(torch.float32).contiguous()
     beta = uniform(seed, w, (w.B, w.L, w.H), 0.05, 0.95, chunk, 0, _TBETA)
     return alpha, beta
+
+
+def feature_weights(w: Workload, seed: int = 0) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Stand-ins for the learned per-head 1x1 maps phi_q, phi_k, phi_v: [H, D, D] indexed [head, out, in],
+    identity plus N(0, 1/(4 D)) noise (a map adapted from, and still close to, the pretrained
+    representation), stored in the workload's dtype."""
+    eye = np.eye(w.D, dtype=np.float64)[None]
+    out = []
+    for tag in (_WQ, _WK, _WV):
+        noise = _generator(seed, w.name, 0, 0, tag).standard_normal((w.H, w.D, w.D)) * (0.5 / np.sqrt(w.D))
+        out.append(_store(eye + noise, w.io_dtype))
+    return tuple(out)
+
+
+def rope_tables(w: Workload, grid: Tuple[int, int] = (30, 52)) -> Tuple[torch.Tensor, torch.Tensor]:
+    """cos, sin [L, D/2] fp32 of a three-axis rotary embedding over (latent frame, row, column): token l
+    sits at (l // (rows * cols), (l // cols) % rows, l % cols); the D/2 pairs are split over the three axes
+    (the first takes the remainder), each axis with frequencies 10000 ** (-i / n_axis)."""
+    rows, cols = grid
+    l = np.arange(w.L)
+    pos = np.stack([l // (rows * cols), (l // cols) % rows, l % cols], axis=1).astype(np.float64)
+    half = w.D // 2
+    n_sp = half // 3
+    sizes = [half - 2 * n_sp, n_sp, n_sp]
+    ang = np.concatenate([pos[:, a:a + 1] * (10000.0 ** (-np.arange(n) / max(n, 1)))[None, :]
+                          for a, n in enumerate(sizes)], axis=1)
+    return (torch.from_numpy(np.cos(ang).astype(np.float32)).contiguous(),
+            torch.from_numpy(np.sin(ang).astype(np.float32)).contiguous())
 
 
 def as_f32_numpy(t: torch.Tensor) -> np.ndarray:
