@@ -98,7 +98,26 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
         ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
     rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
 
+    fm = None
+    if args.feature_maps:
+        if w.io_dtype != "bf16":
+            print("bench.py: --feature-maps needs a bf16 workload", file=sys.stderr)
+            return 2
+        Wq, Wk, Wv = (t.to(dev) for t in W.feature_weights(w))
+        cs, sn = (t.to(dev) for t in W.rope_tables(w))
+        fm = {"Wq": Wq, "Wk": Wk, "Wv": Wv, "cs": cs, "sn": sn, "ql": torch.empty_like(kc),
+              "kl": torch.empty_like(kc), "vl": torch.empty_like(kc)}
+
     def commit():
+        if fm is not None:
+            A.arl2_feature_map(kc, fm["Wk"], fm["cs"], fm["sn"], fm["kl"])
+            A.arl2_feature_map(vc, fm["Wv"], None, None, fm["vl"])
+            kk, vv = fm["kl"], fm["vl"]
+        else:
+            kk, vv = kc, vc
+        _commit(kk, vv)
+
+    def _commit(kc, vc):
         if rule == "plain":
             A.arl2_state_commit(kc, vc, gate, S, ws)
         elif rule == "delta":
@@ -155,6 +174,10 @@ def main() -> int:
     ap.add_argument("--commit-rule", default="plain", choices=["plain", "delta", "gdn"],
                     help="state update of the step: plain (the headline: gate * S + K'^T V), delta (Eq. (4) at frame "
                          "level, one learning rate per head), gdn (Eq. (4) token by token, per-token gates)")
+    ap.add_argument("--feature-maps", action="store_true",
+                    help="put the learned per-head maps of Eq. (3) on the path: every readout pass first computes "
+                         "q_lin = RoPE(phi_q(Q)) (arl2_feature_map) and reads the state with it; the commit is preceded by "
+                         "RoPE(phi_k(K)) and phi_v(V) of the clean pass.  Not the headline configuration.")
     ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stack-report", action="store_true",
@@ -212,7 +235,26 @@ def main() -> int:
         ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
     rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
 
+    fm = None
+    if args.feature_maps:
+        if w.io_dtype != "bf16":
+            print("bench.py: --feature-maps needs a bf16 workload", file=sys.stderr)
+            return 2
+        Wq, Wk, Wv = (t.to(dev) for t in W.feature_weights(w))
+        cs, sn = (t.to(dev) for t in W.rope_tables(w))
+        fm = {"Wq": Wq, "Wk": Wk, "Wv": Wv, "cs": cs, "sn": sn, "ql": torch.empty_like(kc),
+              "kl": torch.empty_like(kc), "vl": torch.empty_like(kc)}
+
     def commit():
+        if fm is not None:
+            A.arl2_feature_map(kc, fm["Wk"], fm["cs"], fm["sn"], fm["kl"])
+            A.arl2_feature_map(vc, fm["Wv"], None, None, fm["vl"])
+            kk, vv = fm["kl"], fm["vl"]
+        else:
+            kk, vv = kc, vc
+        _commit(kk, vv)
+
+    def _commit(kc, vc):
         if rule == "plain":
             A.arl2_state_commit(kc, vc, gate, S, ws)
         elif rule == "delta":
@@ -233,7 +275,11 @@ def main() -> int:
             e0.record()
         for p in range(w.passes):
             q, k, v, g = passes[p]
-            A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
+            if fm is not None:
+                A.arl2_feature_map(q, fm["Wq"], fm["cs"], fm["sn"], fm["ql"])
+                A.arl2_hybrid_attn_fwd_ex(q, k, v, fm["ql"], S, g, outs[p])
+            else:
+                A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
         if events is not None:
             e1 = torch.cuda.Event(enable_timing=True)
             e1.record()
@@ -273,7 +319,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "commit_rule": rule, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
+                   "passes": w.passes, "commit_rule": rule, "feature_maps": bool(args.feature_maps), "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,
         "token_passes_per_s": w.B * w.L * w.passes / (ms_per_step * 1e-3),
@@ -291,7 +337,7 @@ def main() -> int:
         t = json.load(open(traffic_file)).get(w.name)
         if t:
             result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and fm is None:
         result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps, rule, rule_cpu)
     print(json.dumps(result), flush=True)
     return 0

@@ -6,17 +6,25 @@
 //
 // HBM-bound (x read once, y written once, 2 D flop per byte).  Computed transposed,
 //   y^T[e][l] = sum_d W[e][d] x[l][d],
-// so that both operands are read as rows (A = rows of W, B = rows of x, 16 bytes per lane straight
-// from global memory) and a lane ends up with one token's outputs, four consecutive features per
-// register quad: the two members of every rotation pair sit in the same lane.  One wavefront owns 32
-// tokens of one head; results are transposed through LDS so that every output row is written as
-// contiguous 16-byte pieces.
+// so that a lane ends up with one token's outputs, four consecutive features per register quad: the
+// two members of every rotation pair sit in the same lane.
+//
+// One workgroup owns four consecutive heads (wavefront = head) and one to four tiles of 32 tokens
+// (four when there are enough workgroups to fill the chip several times over).  The
+// rows of four heads are 4 D contiguous bf16 per token, so the tile moves between HBM and LDS in
+// whole 1 KB rows (D = 128); the rotation table of the tile, which all heads share, is staged once per
+// tile.  Each wavefront keeps its head's W as MFMA A-operand fragments in registers for all four tiles,
+// reads its x fragments (B operand) from the LDS tile, and writes its rotated outputs back into the
+// same tile, which then leaves as whole rows.
 #include "arl2_device.h"
 
 namespace arl2 {
 namespace {
 
-constexpr int NT = 256;    // four wavefronts, 32 tokens each
+constexpr int NT = 256;    // four wavefronts = four heads
+constexpr int HG = 4;      // heads per workgroup
+constexpr int TT = 32;     // tokens per tile
+constexpr int MAX_NTILE = 4;   // most tiles per workgroup (W stays in registers across them)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
@@ -24,90 +32,124 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
 }
 
 template <int D>
-__global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_tiles)
+__global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ranges, int n_hg, int ntile)
 {
     constexpr int KS = D / 16, EB = D / 32, CPR = D / 8;
-    constexpr int OROW = 2 * D + 16;                     // LDS bytes per staged output row
-    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * OROW];
+    constexpr int HROW = 2 * D + 16;                     // LDS bytes per (token, head) row
+    constexpr int TROW = HG * HROW + 16;                 // LDS bytes per token (conflict-free 16-byte column reads)
+    constexpr int X_BYTES = TT * TROW;
+    constexpr int TST = D / 2 + 2;                       // floats per token of a staged table (conflict-free 8-byte reads)
+    constexpr int XCH = TT * HG * CPR / NT;              // 16-byte chunks of the x tile per thread
+    constexpr int TCH = TT * (D / 8) / NT;               // 16-byte chunks of one table tile per thread
+    static_assert(XCH >= 1 && TCH >= 1, "tile too small for the workgroup");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[X_BYTES + 2 * TT * TST * 4];
+    float *cosT = (float *)(smem + X_BYTES), *sinT = cosT + TT * TST;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c = lane & 31;
-    const int tile = blockIdx.x % n_tiles;
-    const int bh = blockIdx.x / n_tiles;
-    const int h = bh % a.H, b = bh / a.H;
+    const int rng = blockIdx.x % n_ranges;
+    const int hg = (blockIdx.x / n_ranges) % n_hg;
+    const int b = blockIdx.x / (n_ranges * n_hg);
     const int L = a.L, H = a.H;
-    const int l0 = tile * 128 + wave * 32;               // this wavefront's first token
-    const int l = l0 + c;                                // this lane's token
+    const int h = hg * HG + wave;
+    const bool active = h < H;
+    const bool rope = a.cs != nullptr;
+
+    // the whole x and y arrays as buffers: out-of-range chunks read zero / are dropped
     const uint32_t tok_bytes = (uint32_t)H * D * 2;
-    const bf16_t *xg = (const bf16_t *)a.x + ((size_t)b * L * H + h) * D;
-    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xg, (uint32_t)(L - 1) * tok_bytes + 2 * D);
+    const uint32_t total = (uint32_t)a.B * L * tok_bytes;
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(a.x, total);
+    const __amdgpu_buffer_rsrc_t y_rsrc = make_rsrc(a.y, total);
+    const uint32_t tab_bytes = (uint32_t)L * (D / 2) * 4;
+    const __amdgpu_buffer_rsrc_t c_rsrc = make_rsrc(rope ? a.cs : a.x, rope ? tab_bytes : 0);
+    const __amdgpu_buffer_rsrc_t s_rsrc = make_rsrc(rope ? a.sn : a.x, rope ? tab_bytes : 0);
 
-    // B operand: lane (token c, hh) holds x[l][16 t + 8 hh + 0..7]; tokens past the end read as zero
-    bf16x8 xf[KS];
-#pragma unroll
-    for (int t = 0; t < KS; ++t) {
-        union { u32x4 u; bf16x8 v; } cv;
-        cv.u = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, (uint32_t)l * tok_bytes + 32 * t + 16 * hh, 0, 0);
-        xf[t] = cv.v;
-    }
-
-    // A operand: lane (row e = 32 eb + c, hh) holds W[h][e][16 t + 8 hh + 0..7]
-    const bf16_t *Wg = (const bf16_t *)a.W + (size_t)h * D * D + (size_t)c * D + 8 * hh;
-    f32x16 acc[EB];
-#pragma unroll
-    for (int eb = 0; eb < EB; ++eb) {
-        bf16x8 wf[KS];
-#pragma unroll
-        for (int t = 0; t < KS; ++t) wf[t] = *(const bf16x8 *)(Wg + (size_t)32 * eb * D + 16 * t);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[eb][r] = 0.f;
-#pragma unroll
-        for (int t = 0; t < KS; ++t) acc[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[t], xf[t], acc[eb], 0, 0, 0);
-    }
-
-    // rotation: registers 4 q .. 4 q + 3 of block eb are features e0 .. e0 + 3, e0 = 32 eb + 8 q + 4 hh,
-    // i.e. the pairs e0 / 2 and e0 / 2 + 1
-    if (a.cs != nullptr) {
-        const int lc = l < L ? l : L - 1;
-        const float *cs = a.cs + (size_t)lc * (D / 2) + 2 * hh;
-        const float *sn = a.sn + (size_t)lc * (D / 2) + 2 * hh;
+    // A operand: lane (row e = 32 eb + c, hh) holds W[h][e][16 t + 8 hh + 0..7], kept for all tiles
+    bf16x8 wf[EB][KS];
+    if (active) {
+        const bf16_t *Wg = (const bf16_t *)a.W + (size_t)h * D * D + (size_t)c * D + 8 * hh;
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x2 c2 = *(const f32x2 *)(cs + 16 * eb + 4 * q);
-                const f32x2 s2 = *(const f32x2 *)(sn + 16 * eb + 4 * q);
-#pragma unroll
-                for (int p = 0; p < 2; ++p) {
-                    const float y0 = acc[eb][4 * q + 2 * p], y1 = acc[eb][4 * q + 2 * p + 1];
-                    acc[eb][4 * q + 2 * p] = y0 * c2[p] - y1 * s2[p];
-                    acc[eb][4 * q + 2 * p + 1] = fmaf(y0, s2[p], y1 * c2[p]);
-                }
-            }
+            for (int t = 0; t < KS; ++t) wf[eb][t] = *(const bf16x8 *)(Wg + (size_t)32 * eb * D + 16 * t);
     }
 
-    // transpose through this wavefront's LDS region, then whole rows go out as 16-byte pieces
-    unsigned char *region = smem + wave * 32 * OROW;
+    // chunk i of this thread in a tile: token tk, 16-byte column col of the token's HG heads
+    const uint32_t head0_bytes = (uint32_t)hg * HG * D * 2;
+    for (int tile = 0; tile < ntile; ++tile) {
+        const int l0 = (rng * ntile + tile) * TT;
+        if (l0 >= L) break;                              // uniform over the workgroup
+        // ---- stage the x tile and the table tile
 #pragma unroll
-    for (int eb = 0; eb < EB; ++eb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bf16x4 w4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) w4[i] = to_bf16(acc[eb][4 * q + i]);
-            *(bf16x4 *)(region + c * OROW + 2 * (32 * eb + 8 * q + 4 * hh)) = w4;
+        for (int i = 0; i < XCH; ++i) {
+            const int id = tid + NT * i;
+            const int tk = id / (HG * CPR), col = id % (HG * CPR);
+            const bool ok = l0 + tk < L && hg * HG + col / CPR < H;
+            const uint32_t off = ok ? ((uint32_t)b * L + l0 + tk) * tok_bytes + head0_bytes + 16 * col : total;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0);
+            *(u32x4 *)(smem + tk * TROW + (col / CPR) * HROW + 16 * (col % CPR)) = v;
         }
-    __builtin_amdgcn_wave_barrier();
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is private to this wavefront
-    bf16_t *yg = (bf16_t *)a.y + ((size_t)b * L * H + h) * D;
+        if (rope) {
 #pragma unroll
-    for (int i = 0; i < CPR / 2; ++i) {
-        const int idx = lane + 64 * i;
-        const int row = idx / CPR, col = idx % CPR;
-        if (l0 + row < L) {
-            const u32x4 v = *(const u32x4 *)(region + row * OROW + 16 * col);
-            *(u32x4 *)(yg + (size_t)(l0 + row) * H * D + 8 * col) = v;
+            for (int i = 0; i < TCH; ++i) {
+                const int id = tid + NT * i;
+                const int tk = id / (D / 8), col = id % (D / 8);
+                const uint32_t off = l0 + tk < L ? (uint32_t)(l0 + tk) * (D / 2) * 4 + 16 * col : tab_bytes;
+                const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(c_rsrc, off, 0, 0);
+                const u32x4 sv = __builtin_amdgcn_raw_buffer_load_b128(s_rsrc, off, 0, 0);
+                u32x2 *cd = (u32x2 *)(cosT + tk * TST + 4 * col), *sd = (u32x2 *)(sinT + tk * TST + 4 * col);
+                cd[0] = u32x2{cv[0], cv[1]};
+                cd[1] = u32x2{cv[2], cv[3]};
+                sd[0] = u32x2{sv[0], sv[1]};
+                sd[1] = u32x2{sv[2], sv[3]};
+            }
         }
+        __syncthreads();
+        // ---- B operand: lane (token c, hh) holds x[l0 + c][h][16 t + 8 hh + 0..7]
+        bf16x8 xf[KS];
+        unsigned char *mine = smem + c * TROW + wave * HROW;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) xf[t] = *(const bf16x8 *)(mine + 32 * t + 16 * hh);
+        __syncthreads();                                 // every wavefront holds its fragments: the tile may be overwritten
+        if (active) {
+#pragma unroll
+            for (int eb = 0; eb < EB; ++eb) {
+                f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int t = 0; t < KS; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[eb][t], xf[t], acc, 0, 0, 0);
+                // registers 4 q .. 4 q + 3 are features e0 .. e0 + 3, e0 = 32 eb + 8 q + 4 hh: pairs e0 / 2, e0 / 2 + 1
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float y[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+                    if (rope) {
+                        const f32x2 c2 = *(const f32x2 *)(cosT + c * TST + 16 * eb + 4 * q + 2 * hh);
+                        const f32x2 s2 = *(const f32x2 *)(sinT + c * TST + 16 * eb + 4 * q + 2 * hh);
+#pragma unroll
+                        for (int p = 0; p < 2; ++p) {
+                            const float y0 = y[2 * p], y1 = y[2 * p + 1];
+                            y[2 * p] = y0 * c2[p] - y1 * s2[p];
+                            y[2 * p + 1] = fmaf(y0, s2[p], y1 * c2[p]);
+                        }
+                    }
+                    bf16x4 w4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w4[i] = to_bf16(y[i]);
+                    *(bf16x4 *)(mine + 2 * (32 * eb + 8 * q + 4 * hh)) = w4;
+                }
+            }
+        }
+        __syncthreads();
+        // ---- the tile leaves as whole rows
+#pragma unroll
+        for (int i = 0; i < XCH; ++i) {
+            const int id = tid + NT * i;
+            const int tk = id / (HG * CPR), col = id % (HG * CPR);
+            const bool ok = l0 + tk < L && hg * HG + col / CPR < H;
+            const u32x4 v = *(const u32x4 *)(smem + tk * TROW + (col / CPR) * HROW + 16 * (col % CPR));
+            const uint32_t off = ok ? ((uint32_t)b * L + l0 + tk) * tok_bytes + head0_bytes + 16 * col : total;
+            __builtin_amdgcn_raw_buffer_store_b128(v, y_rsrc, off, 0, 0);
+        }
+        __syncthreads();                                 // the next tile's rows may be written
     }
 }
 
@@ -115,15 +157,21 @@ __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ti
 
 hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream)
 {
-    const int n_tiles = (a.L + 127) / 128;
-    const long long nwg = (long long)a.B * a.H * n_tiles;
+    const int n_hg = (a.H + HG - 1) / HG;
+    const int tiles = (a.L + TT - 1) / TT;
+    // more tiles per workgroup amortise the W fragments, fewer give more workgroups: keep about 3 per CU
+    long long ntile = (long long)a.B * n_hg * tiles / 768;
+    if (ntile < 1) ntile = 1;
+    if (ntile > MAX_NTILE) ntile = MAX_NTILE;
+    const int n_ranges = (tiles + (int)ntile - 1) / (int)ntile;
+    const long long nwg = (long long)a.B * n_hg * n_ranges;
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
-    // one stream's x is addressed with 32-bit byte offsets
-    if ((long long)(a.L + 128) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
+    // x and y are addressed with 32-bit byte offsets
+    if ((long long)a.B * a.L * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.D == 128)
-        hipLaunchKernelGGL(feature_map_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_tiles);
+        hipLaunchKernelGGL(feature_map_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_ranges, n_hg, (int)ntile);
     else if (a.D == 64)
-        hipLaunchKernelGGL(feature_map_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_tiles);
+        hipLaunchKernelGGL(feature_map_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_ranges, n_hg, (int)ntile);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
