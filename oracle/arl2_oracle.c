@@ -356,6 +356,26 @@ int arl2o_feature_map_f64(int B, int H, int L, int D,
     return 0;
 }
 
+/*
+ * Headwise branch-mix gate, Eq. (6): G = sigmoid(x W_g), x [B][L][dm] the layer's hidden state
+ * (dm = H * D), W_g given per head as Wg[H][dm] (column h of the paper's dm x H matrix), G [B][L][H].
+ */
+int arl2o_gate_proj_f64(int B, int L, int dm, int H,
+                        const float *x, const float *Wg, double *G)
+{
+#pragma omp parallel for schedule(static)
+    for (long t = 0; t < (long)B * L; ++t) {
+        const float *x_row = x + (size_t)t * dm;
+        for (int h = 0; h < H; ++h) {
+            double acc = 0.0;
+            for (int j = 0; j < dm; ++j)
+                acc += (double)x_row[j] * (double)Wg[(size_t)h * dm + j];
+            G[(size_t)t * H + h] = 1.0 / (1.0 + exp(-acc));
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- fp32 -- */
 /* The same two definitions with every operation in float: the reference for
  * the configuration that is specified as fp32 throughout.                    */

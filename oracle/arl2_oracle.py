@@ -56,6 +56,8 @@ def _load():
         lib.arl2o_fwd_ex_f64.restype = i32
         lib.arl2o_feature_map_f64.argtypes = [i32] * 4 + [vp] * 5
         lib.arl2o_feature_map_f64.restype = i32
+        lib.arl2o_gate_proj_f64.argtypes = [i32] * 4 + [vp] * 3
+        lib.arl2o_gate_proj_f64.restype = i32
         lib.arl2o_commit_gdn_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
         lib.arl2o_commit_gdn_f64.restype = i32
         lib.arl2o_num_threads.restype = i32
@@ -212,6 +214,20 @@ def feature_map(x, W, cos=None, sin=None) -> np.ndarray:
     if rc != 0:
         raise MemoryError("oracle feature_map failed")
     return y
+
+
+def gate_proj(x, Wg) -> np.ndarray:
+    """Headwise mix gate of Eq. (6): sigmoid(x W_g).  x [B, L, dm]; Wg [H, dm] (one row per head); fp64 [B, L, H]."""
+    lib = _load()
+    x, Wg = _c(x, np.float32), _c(Wg, np.float32)
+    if x.ndim != 3 or Wg.ndim != 2 or Wg.shape[1] != x.shape[2]:
+        raise ValueError("x must be [B, L, dm] and Wg [H, dm]")
+    B, L, dm = x.shape
+    H = Wg.shape[0]
+    G = np.empty((B, L, H), dtype=np.float64)
+    if lib.arl2o_gate_proj_f64(B, L, dm, H, _ptr(x), _ptr(Wg), _ptr(G)) != 0:
+        raise MemoryError("oracle gate_proj failed")
+    return G
 
 
 def rollout(chunks, S0=None, *, l2_eps: float = L2_EPS, precision: str = "f64", rows=None):

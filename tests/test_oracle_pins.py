@@ -534,3 +534,25 @@ def test_inter_branch_reads_its_own_query(oracle):
     inter = np.einsum("blhd,bhde->blhe", l2n(ql, eps), S) * g[..., None].astype(np.float64)
     np.testing.assert_allclose(oracle.fwd(q, k, v, S, g, q_lin=ql), intra + inter, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(oracle.fwd(q, k, v, S, g, q_lin=3.0 * ql), intra + inter, rtol=1e-5, atol=1e-5)   # up to eps and the fp32 rounding of 3 q
+
+
+# ---------------------------------------------------------------- headwise mix gate, Eq. (6)
+
+def test_gate_proj_pins(oracle):
+    from scipy.special import expit
+    B, L, dm, H = 2, 11, 24, 3
+    x, Wg = rand(B, L, dm), rand(H, dm, scale=0.3)
+    G = oracle.gate_proj(x, Wg)
+    np.testing.assert_allclose(G, expit(np.einsum("blj,hj->blh", x.astype(np.float64), Wg.astype(np.float64))), rtol=1e-13)
+    assert G.shape == (B, L, H) and np.all((G > 0) & (G < 1))
+    # zero weights: every gate is one half; a head's gate depends on that head's weight row only
+    np.testing.assert_array_equal(oracle.gate_proj(x, np.zeros_like(Wg)), np.full((B, L, H), 0.5))
+    W2 = Wg.copy()
+    W2[1] = 0.0
+    G2 = oracle.gate_proj(x, W2)
+    np.testing.assert_array_equal(G2[..., 0], G[..., 0])
+    np.testing.assert_array_equal(G2[..., 1], np.full((B, L), 0.5))
+    # hand example: x = (1, 2), w = (ln 3, 0) -> sigmoid(ln 3) = 3/4; w = (0, -ln(3)/2) -> sigmoid(-ln 3) = 1/4
+    xh = np.array([[[1.0, 2.0]]], dtype=np.float32)
+    wh = np.array([[math.log(3.0), 0.0], [0.0, -math.log(3.0) / 2.0]], dtype=np.float32)
+    np.testing.assert_allclose(oracle.gate_proj(xh, wh)[0, 0], [0.75, 0.25], rtol=1e-7)
