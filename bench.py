@@ -98,6 +98,13 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
         ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
     rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
 
+    gp = None
+    if args.gate_proj:
+        if w.io_dtype != "bf16":
+            print("bench.py: --gate-proj needs a bf16 workload", file=sys.stderr)
+            return 2
+        gp = [tuple(t.to(dev) for t in W.gate_inputs(w, 0, p)) for p in range(w.passes)]
+    n_read = w.passes + (1 if args.clean_readout else 0)
     fm = None
     if args.feature_maps:
         if w.io_dtype != "bf16":
@@ -178,6 +185,12 @@ def main() -> int:
                     help="put the learned per-head maps of Eq. (3) on the path: every readout pass first computes "
                          "q_lin = RoPE(phi_q(Q)) (arl2_feature_map) and reads the state with it; the commit is preceded by "
                          "RoPE(phi_k(K)) and phi_v(V) of the clean pass.  Not the headline configuration.")
+    ap.add_argument("--gate-proj", action="store_true",
+                    help="compute the mix gate of every readout pass on the path, G = sigmoid(x W_g) (arl2_gate_proj), "
+                         "instead of taking it as an input.  Not the headline configuration.")
+    ap.add_argument("--clean-readout", action="store_true",
+                    help="one more readout pass per step, on the clean pass's inputs before the commit "
+                         "(passes + 1 readouts, then the commit).  Not the headline configuration.")
     ap.add_argument("--cpu-steps", type=int, default=3, help="whole chunk steps timed on the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stack-report", action="store_true",
@@ -235,6 +248,13 @@ def main() -> int:
         ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
     rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
 
+    gp = None
+    if args.gate_proj:
+        if w.io_dtype != "bf16":
+            print("bench.py: --gate-proj needs a bf16 workload", file=sys.stderr)
+            return 2
+        gp = [tuple(t.to(dev) for t in W.gate_inputs(w, 0, p)) for p in range(w.passes)]
+    n_read = w.passes + (1 if args.clean_readout else 0)
     fm = None
     if args.feature_maps:
         if w.io_dtype != "bf16":
@@ -273,13 +293,15 @@ def main() -> int:
         if events is not None:
             e0 = torch.cuda.Event(enable_timing=True)
             e0.record()
-        for p in range(w.passes):
-            q, k, v, g = passes[p]
+        for p in range(n_read):
+            q, k, v, g = passes[p % w.passes]
+            if gp is not None:
+                A.arl2_gate_proj(gp[p % w.passes][0], gp[p % w.passes][1], g)
             if fm is not None:
                 A.arl2_feature_map(q, fm["Wq"], fm["cs"], fm["sn"], fm["ql"])
-                A.arl2_hybrid_attn_fwd_ex(q, k, v, fm["ql"], S, g, outs[p])
+                A.arl2_hybrid_attn_fwd_ex(q, k, v, fm["ql"], S, g, outs[p % w.passes])
             else:
-                A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
+                A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p % w.passes])
         if events is not None:
             e1 = torch.cuda.Event(enable_timing=True)
             e1.record()
@@ -301,14 +323,14 @@ def main() -> int:
     ms_per_step = 1e3 * t_total / args.steps
     # readout launch time: span of the `passes` back-to-back launches of a step / passes;
     # commit time: from the end of a step's last readout pass to the start of the next step
-    fwd_ms = [e0.elapsed_time(e1) / w.passes for (e0, e1) in events]
+    fwd_ms = [e0.elapsed_time(e1) / n_read for (e0, e1) in events]
     nxt = [e[0] for e in events[1:]] + [end]
     com_ms = [events[i][1].elapsed_time(nxt[i]) for i in range(len(events))]
     fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
     com_avg_ms = sum(com_ms) / len(com_ms)
 
     ff, cf = fwd_flops(w.B, w.H, w.L, w.D), commit_flops(w.B, w.H, w.L, w.D)
-    step_flops = w.passes * ff + cf
+    step_flops = n_read * ff + cf
     fwd_tflops = ff / (fwd_avg_ms * 1e-3) / 1e12
     step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
     result = {
@@ -319,10 +341,11 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "commit_rule": rule, "feature_maps": bool(args.feature_maps), "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
+                   "passes": w.passes, "commit_rule": rule, "feature_maps": bool(args.feature_maps), "gate_proj": bool(args.gate_proj),
+                   "readouts_per_step": n_read, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,
-        "token_passes_per_s": w.B * w.L * w.passes / (ms_per_step * 1e-3),
+        "token_passes_per_s": w.B * w.L * n_read / (ms_per_step * 1e-3),
         "fwd_ms": fwd_avg_ms, "fwd_ms_min": min(fwd_ms),
         "commit_ms": com_avg_ms, "commit_ms_min": min(com_ms),
         "commit_gbs": commit_bytes(w.B, w.H, w.L, w.D, io_bytes, rule) / (com_avg_ms * 1e-3) / 1e9,
@@ -337,7 +360,7 @@ def main() -> int:
         t = json.load(open(traffic_file)).get(w.name)
         if t:
             result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
-    if not args.no_cpu_baseline and fm is None:
+    if not args.no_cpu_baseline and fm is None and gp is None and not args.clean_readout:
         result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps, rule, rule_cpu)
     print(json.dumps(result), flush=True)
     return 0

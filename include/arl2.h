@@ -21,7 +21,8 @@
  *   arl2_state_commit_gdn  Eq. (4) applied token by token in order, with per-token gates.
  *
  *   arl2_feature_map       the learned per-head maps and RoPE of Eq. (3) for the linear branch;
- *   arl2_hybrid_attn_fwd_ex  the readout pass with the linear branch's own query.
+ *   arl2_hybrid_attn_fwd_ex  the readout pass with the linear branch's own query;
+ *   arl2_gate_proj         the headwise gate G = sigmoid(x W_g) of Eq. (6).
  *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
@@ -122,6 +123,16 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc,
  */
 arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W,
                              const float *rope_cos, const float *rope_sin, void *y);
+
+/*
+ * Headwise branch-mix gate, paper Eq. (6): G = sigmoid(x W_g), the g argument of the readout pass.
+ *   x         device bf16 [B][Lq][H*D], the layer's hidden state (desc->io_dtype must be ARL2_BF16).
+ *   Wg        device bf16 [H][H*D]: row h is column h of the paper's (H*D) x H matrix W_g.
+ *   g         device [B][Lq][H] in desc->g_dtype, fully overwritten; must not alias an input.
+ * Up to 32 heads.  fp32 accumulation and sigmoid.  (A gate per token shared by all heads, or any other
+ * gate already in [B][Lq][H] form, needs no kernel of its own: the readout takes it as it is.)
+ */
+arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg, void *g);
 
 /*
  * Post-denoise state update (paper Eq. (3), Eq. (4); Alg. 1 clean pass).

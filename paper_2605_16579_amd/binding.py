@@ -19,7 +19,7 @@ ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ER
 ARL2_F32, ARL2_BF16 = 0, 1
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
-           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_feature_map",
+           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_feature_map", "arl2_gate_proj",
            "arl2_status_string", "arl2_last_error", "arl2_version"]
 
 
@@ -62,6 +62,8 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_hybrid_attn_fwd_ex.restype = ctypes.c_int
         lib.arl2_feature_map.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_feature_map.restype = ctypes.c_int
+        lib.arl2_gate_proj.argtypes = [dp, vp, vp, vp]
+        lib.arl2_gate_proj.restype = ctypes.c_int
         lib.arl2_gdn_workspace_bytes.argtypes = [dp]
         lib.arl2_gdn_workspace_bytes.restype = ctypes.c_size_t
         lib.arl2_state_commit_gdn.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -180,6 +182,21 @@ def arl2_feature_map(x: torch.Tensor, W: torch.Tensor, rope_cos: Optional[torch.
         ctypes.byref(d), _dev(x, "x"), _dev(W, "W", (H, D, D), x.dtype),
         _dev(rope_cos, "rope_cos", (L, D // 2), torch.float32), _dev(rope_sin, "rope_sin", (L, D // 2), torch.float32),
         _dev(y, "y", (B, L, H, D), x.dtype))
+    _check(st)
+
+
+def arl2_gate_proj(x: torch.Tensor, Wg: torch.Tensor, g: torch.Tensor, *, stream: Optional[int] = None) -> None:
+    """g = sigmoid(x Wg^T): the headwise mix gate of Eq. (6).  x [B, L, H*D] bf16, Wg [H, H*D] bf16,
+    g [B, L, H] fp32 or bf16 (written)."""
+    if x.dim() != 3 or Wg.dim() != 2:
+        raise ValueError("x must be [B, L, H*D] and Wg [H, H*D]")
+    B, L, dm = x.shape
+    H = Wg.shape[0]
+    if dm % H:
+        raise ValueError("the hidden size must be a multiple of the number of heads")
+    d = make_desc(B, H, L, L, dm // H, _dtype_code(x), _dtype_code(g), stream=stream)
+    st = load_library().arl2_gate_proj(ctypes.byref(d), _dev(x, "x"), _dev(Wg, "Wg", (H, dm), x.dtype),
+                                       _dev(g, "g", (B, L, H)))
     _check(st)
 
 

@@ -115,6 +115,26 @@ arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W
     return ARL2_OK;
 }
 
+arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg, void *g)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!x || !Wg || !g) return fail(ARL2_ERR_INVALID_ARG, "x, Wg and g must not be NULL");
+    if (!aligned16(x) || !aligned16(Wg)) return fail(ARL2_ERR_INVALID_ARG, "x and Wg must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(g) & 3u) return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
+    if (g == x || g == Wg) return fail(ARL2_ERR_INVALID_ARG, "g must not alias an input");
+    if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj takes bf16 x, Wg only");
+    if (desc->H > 32) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj supports up to 32 heads");
+
+    arl2::GateArgs a;
+    a.x = x; a.Wg = Wg; a.g = g;
+    a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.dm = desc->H * desc->D;
+    a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
+    const hipError_t e = arl2::launch_gate_proj_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "gate projection launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
 static arl2_status commit_common(const arl2_desc *desc, const void *k, const void *v, const float *gate,
                                  const float *beta, bool delta, float *S)
 {

@@ -54,6 +54,14 @@ struct FmapArgs {
     int B, H, L, D;
 };
 
+struct GateArgs {
+    const void *x;         // [B][L][dm] bf16, dm = H * D
+    const void *Wg;        // [H][dm] bf16
+    void *g;               // [B][L][H], fp32 or bf16
+    int B, H, L, dm;
+    int g_is_bf16;
+};
+
 struct GdnArgs {
     const void *k, *v;
     const float *alpha;    // per-token forget gate  [B][L][H]
@@ -74,6 +82,7 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream);
 hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream);
+hipError_t launch_gate_proj_bf16(const GateArgs &a, hipStream_t stream);
 
 // Workspace of the token-sequential commit (per-block transition maps).
 size_t gdn_workspace_bytes(int B, int H, int L, int D);

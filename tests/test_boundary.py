@@ -127,6 +127,17 @@ def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
     assert ex(d, ql=0x5000) == 1                          # out aliases q_lin
 
 
+def test_gate_proj_rejects_bad_arguments(A):
+    lib = A.load_library()
+    d = A.make_desc(1, 12, 64, 64, 128, A.ARL2_BF16, stream=0)
+    gp = lambda d, x=0x1000, W=0x2000, g=0x3000: lib.arl2_gate_proj(ctypes.byref(d), x, W, g)
+    assert gp(d, x=None) == 1
+    assert gp(d, W=0x2008) == 1
+    assert gp(d, g=0x1000) == 1
+    assert gp(A.make_desc(1, 12, 64, 64, 128, A.ARL2_F32, stream=0)) == 2
+    assert gp(A.make_desc(1, 40, 64, 64, 64, A.ARL2_BF16, stream=0)) == 2      # more than 32 heads
+
+
 def test_binding_refuses_host_tensors(A):
     import torch
     q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16)

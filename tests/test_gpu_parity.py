@@ -553,3 +553,42 @@ def test_feature_map_chain_full_size(lib, oracle):
     e_out, e_state = _feature_chain(lib, oracle, w, rows=sample_rows(w.L, 64, seed=3))
     print(f"[wan_layer] feature-map chain: out {e_out:.3e}, state {e_state:.3e}", flush=True)
     assert e_out <= TOL_BF16_OUT and e_state <= 2e-3
+
+
+# ---------------------------------------------------------------- headwise mix gate, Eq. (6)
+
+@pytest.mark.parametrize("B,L,H,D,gdt", [(2, 328, 3, 128, "f32"), (1, 200, 12, 128, "bf16"), (1, 33, 5, 64, "f32"), (1, 1, 32, 64, "f32")])
+def test_gate_projection_small(lib, oracle, B, L, H, D, gdt):
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gate{H}x{D}", B=B, L=L, H=H, D=D)
+    x, Wg = W.gate_inputs(w, 0, 0)
+    Wg = Wg * 8.0                                            # wider logits than the recipe: gates from about 0.1 to 0.9
+    g = torch.full((B, L, H), -1.0, dtype=torch.float32 if gdt == "f32" else torch.bfloat16, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    torch.cuda.synchronize()
+    ref = oracle.gate_proj(to_np(x), to_np(Wg))
+    assert ref.min() < 0.3 and ref.max() > 0.7
+    err = np.abs(to_np(g) - ref).max()
+    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9), f"{err:.3e}"
+
+
+def test_gate_projection_feeds_the_readout_full_size(lib, oracle):
+    """Headline shape: G = sigmoid(x W_g) on the GPU against the oracle, then used as the readout's gate."""
+    w = W.WORKLOADS["wan_layer"]
+    x, Wg = W.gate_inputs(w, 0, 0)
+    g = torch.empty((w.B, w.L, w.H), dtype=torch.float32, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    torch.cuda.synchronize()
+    g_ref = oracle.gate_proj(to_np(x), to_np(Wg))
+    err = np.abs(to_np(g) - g_ref).max()
+    print(f"[wan_layer] gate projection: max abs err {err:.3e}, gates in [{g_ref.min():.3f}, {g_ref.max():.3f}]", flush=True)
+    assert err <= 2e-6
+    q, k, v, _ = W.pass_inputs(w, 0, 0)
+    S0 = W.normal(16, w, (w.B, w.H, w.D, w.D), 0, 0, 98, io_dtype="f32") * 0.2
+    rows = sample_rows(w.L, 32, seed=5)
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S0), g, out)
+    torch.cuda.synchronize()
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S0).astype(np.float64), g_ref.astype(np.float32), rows=rows)
+    e = rel_err(to_np(out)[:, rows], ref)
+    assert e <= TOL_BF16_OUT, f"{e:.3e}"

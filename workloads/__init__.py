@@ -82,7 +82,7 @@ def uniform(seed: int, w: Workload, shape, lo: float, hi: float, *ids: int) -> t
 
 
 # tensor tags
-_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE, _TALPHA, _TBETA, _WQ, _WK, _WV = range(15)
+_Q, _K, _V, _G, _KC, _VC, _GATE, _PK, _PV, _PGATE, _TALPHA, _TBETA, _WQ, _WK, _WV, _XH, _WG = range(17)
 
 
 def pass_inputs(w: Workload, chunk: int, p: int, seed: int = 0
@@ -139,6 +139,15 @@ def feature_weights(w: Workload, seed: int = 0) -> Tuple[torch.Tensor, torch.Ten
         noise = _generator(seed, w.name, 0, 0, tag).standard_normal((w.H, w.D, w.D)) * (0.5 / np.sqrt(w.D))
         out.append(_store(eye + noise, w.io_dtype))
     return tuple(out)
+
+
+def gate_inputs(w: Workload, chunk: int, p: int, seed: int = 0) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Hidden state x [B, L, H*D] ~ N(0,1) and gate weights Wg [H, H*D] ~ N(0, 0.01 / (H*D)) in the stored
+    dtype: logits with standard deviation 0.1, i.e. gates spread over about 0.45..0.55 like the learned ones."""
+    dm = w.H * w.D
+    x = _store(_generator(seed, w.name, chunk, p, _XH).standard_normal((w.B, w.L, dm), dtype=np.float32), w.io_dtype)
+    Wg = _store(_generator(seed, w.name, 0, 0, _WG).standard_normal((w.H, dm)) * (0.1 / np.sqrt(dm)), w.io_dtype)
+    return x, Wg
 
 
 def rope_tables(w: Workload, grid: Tuple[int, int] = (30, 52)) -> Tuple[torch.Tensor, torch.Tensor]:
