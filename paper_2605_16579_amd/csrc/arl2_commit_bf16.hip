@@ -24,6 +24,8 @@
 // Gram matrix with a snapshot of the old state in fp32.
 #include "arl2_device.h"
 
+#include <type_traits>
+
 namespace arl2 {
 namespace {
 
@@ -44,6 +46,21 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+constexpr int PFT = 3;     // tiles whose loads are in flight (register ring): HBM latency is several tile times
+#ifndef COMMIT_PFW
+#define COMMIT_PFW 3
+#endif
+constexpr int PFW = COMMIT_PFW;   // the same for the producer wavefronts of the plain commit, which hold no accumulators
 
 template <int D, bool DELTA>
 struct CommitCfg {
@@ -86,40 +103,43 @@ __global__ __launch_bounds__(NT, 2) void commit_partial_kernel(CommitArgs a)
     const int t_end = (int)((long long)(split + 1) * ntiles / a.nsplit);
 
     // chunk i of this thread: row (tid / CPR) + ROWS_PER_PASS * i, 16-byte column tid % CPR
-    uint32_t g_off = ((uint32_t)t_begin * BT + tid / C::CPR) * tok_bytes + 16 * (tid % C::CPR);
     const int lds_off = (tid / C::CPR) * C::ROW + 16 * (tid % C::CPR);
-    u32x4 kr[C::KCH], vr[C::KCH];
-    auto load_tile = [&]() {        // rows past the end of the sequence read as zero
+    u32x4 kr[PFT][C::KCH], vr[PFT][C::KCH];
+    // Requests tile `tile` into register buffer `buf` (rows past the end of the sequence read as zero; a
+    // tile that is not this workgroup's is not requested at all: its offsets are put beyond the buffer,
+    // which keeps the loop free of branches around loads).
+    auto load_tile = [&](int tile, auto buf_) {
+        constexpr int buf = decltype(buf_)::value;
+        const uint32_t base = tile < t_end ? ((uint32_t)tile * BT + tid / C::CPR) * tok_bytes + 16 * (tid % C::CPR) : 0x80000000u;
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
-            const uint32_t off = g_off + (uint32_t)i * C::ROWS_PER_PASS * tok_bytes;
-            kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
-            vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
+            const uint32_t off = base + (uint32_t)i * C::ROWS_PER_PASS * tok_bytes;
+            kr[buf][i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
+            vr[buf][i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
         }
-        g_off += BT * tok_bytes;
     };
     // K as it is, and r * V split into bf16 hi + lo, into the LDS stage
-    auto stage_tile = [&](int stage) {
+    auto stage_tile = [&](int stage, auto buf_) {
+        constexpr int buf = decltype(buf_)::value;
         unsigned char *sm = smem + stage * C::STAGE + lds_off;
 #pragma unroll
         for (int i = 0; i < C::KCH; ++i) {
             float ss = 0.f;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float lo = __uint_as_float(kr[i][w] << 16);
-                const float hi = __uint_as_float(kr[i][w] & 0xffff0000u);
+                const float lo = __uint_as_float(kr[buf][i][w] << 16);
+                const float hi = __uint_as_float(kr[buf][i][w] & 0xffff0000u);
                 ss = fmaf(lo, lo, ss);
                 ss = fmaf(hi, hi, ss);
             }
-#pragma unroll
-            for (int off = 1; off < C::CPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
-            const float rn2 = 1.0f / (ss + a.l2_eps);
-            const float rn = 1.0f / sqrtf(ss + a.l2_eps);
+            ss = lane_group_sum<C::CPR>(ss);
+            const float rn = fast_rsqrt(ss + a.l2_eps);
+            const float rn2 = rn * rn;
             union { u32x4 u; bf16x8 v; } vh, vl;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float s0 = __uint_as_float(vr[i][w] << 16) * rn;
-                const float s1 = __uint_as_float(vr[i][w] & 0xffff0000u) * rn;
+                const float s0 = __uint_as_float(vr[buf][i][w] << 16) * rn;
+                const float s1 = __uint_as_float(vr[buf][i][w] & 0xffff0000u) * rn;
                 const bf16_t h0 = to_bf16(s0), h1 = to_bf16(s1);
                 vh.v[2 * w] = h0;
                 vh.v[2 * w + 1] = h1;
@@ -127,15 +147,15 @@ __global__ __launch_bounds__(NT, 2) void commit_partial_kernel(CommitArgs a)
                 vl.v[2 * w + 1] = to_bf16(s1 - (float)h1);
             }
             unsigned char *p = sm + i * C::ROWS_PER_PASS * C::ROW;
-            *(u32x4 *)(p) = kr[i];
+            *(u32x4 *)(p) = kr[buf][i];
             *(u32x4 *)(p + C::MAT) = vh.u;
             *(u32x4 *)(p + 2 * C::MAT) = vl.u;
             if constexpr (DELTA) {
                 union { u32x4 u; bf16x8 v; } kh, kl;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
-                    const float s0 = __uint_as_float(kr[i][w] << 16) * rn2;
-                    const float s1 = __uint_as_float(kr[i][w] & 0xffff0000u) * rn2;
+                    const float s0 = __uint_as_float(kr[buf][i][w] << 16) * rn2;
+                    const float s1 = __uint_as_float(kr[buf][i][w] & 0xffff0000u) * rn2;
                     const bf16_t h0 = to_bf16(s0), h1 = to_bf16(s1);
                     kh.v[2 * w] = h0;
                     kh.v[2 * w + 1] = h1;
@@ -170,40 +190,44 @@ __global__ __launch_bounds__(NT, 2) void commit_partial_kernel(CommitArgs a)
         }
     }
 
-    if (t_begin < t_end) load_tile();
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        const int stage = C::NSTG == 2 ? ((tile - t_begin) & 1) : 0;
-        if constexpr (C::NSTG == 1) __syncthreads();   // single stage: the previous tile's MFMAs are done
-        stage_tile(stage);               // waits for this tile's loads
-        __syncthreads();                 // two stages: every wave is also done with the tile before last
-        if (tile + 1 < t_end) load_tile();
-        if (compute) {
-            const unsigned char *sm = smem + stage * C::STAGE + tr_off;
-            // operand fragments of 16-token step t: tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
-            bf16x8 ka[2][2], bh_[2][C::NACC], bl_[2][C::NACC];
-            auto load_step = [&](int t, int buf) {
-                const unsigned char *row = sm + 16 * t * C::ROW;
+    static_for<0, PFT>([&](auto i_) { load_tile(t_begin + decltype(i_)::value, i_); });
+    for (int tile0 = t_begin; tile0 < t_end; tile0 += PFT) {
+        static_for<0, PFT>([&](auto i_) {
+            const int tile = tile0 + decltype(i_)::value;
+            if (tile >= t_end) return;                  // uniform over the workgroup
+            const int stage = C::NSTG == 2 ? ((tile - t_begin) & 1) : 0;
+            if constexpr (C::NSTG == 1) __syncthreads();   // single stage: the previous tile's MFMAs are done
+            stage_tile(stage, i_);           // waits for this tile's loads
+            __syncthreads();                 // two stages: every wave is also done with the tile before last
+            load_tile(tile + PFT, i_);
+            if (compute) {
+                const unsigned char *sm = smem + stage * C::STAGE + tr_off;
+                // operand fragments of 16-token step t: tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
+                bf16x8 ka[2][2], bh_[2][C::NACC], bl_[2][C::NACC];
+                auto load_step = [&](int t, int buf) {
+                    const unsigned char *row = sm + 16 * t * C::ROW;
 #pragma unroll
-                for (int i = 0; i < 2; ++i) ka[buf][i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
+                    for (int i = 0; i < 2; ++i) ka[buf][i] = lds_read_tr_pair(row + 64 * (d0 + i), 8 * C::ROW);
 #pragma unroll
-                for (int m = 0; m < C::NACC; ++m) {      // m = 0: r V,  m = 1: r^2 K
-                    bh_[buf][m] = lds_read_tr_pair(row + (1 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
-                    bl_[buf][m] = lds_read_tr_pair(row + (2 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
-                }
-            };
-            load_step(0, 0);
-#pragma unroll
-            for (int t = 0; t < BT / 16; ++t) {
-                if (t + 1 < BT / 16) load_step(t + 1, (t + 1) & 1);
-#pragma unroll
-                for (int m = 0; m < C::NACC; ++m)
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bh_[t & 1][m], acc[m][i], 0, 0, 0);
-                        acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bl_[t & 1][m], acc[m][i], 0, 0, 0);
+                    for (int m = 0; m < C::NACC; ++m) {      // m = 0: r V,  m = 1: r^2 K
+                        bh_[buf][m] = lds_read_tr_pair(row + (1 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
+                        bl_[buf][m] = lds_read_tr_pair(row + (2 + 2 * m) * C::MAT + 64 * e0, 8 * C::ROW);
                     }
+                };
+                load_step(0, 0);
+#pragma unroll
+                for (int t = 0; t < BT / 16; ++t) {
+                    if (t + 1 < BT / 16) load_step(t + 1, (t + 1) & 1);
+#pragma unroll
+                    for (int m = 0; m < C::NACC; ++m)
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bh_[t & 1][m], acc[m][i], 0, 0, 0);
+                            acc[m][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bl_[t & 1][m], acc[m][i], 0, 0, 0);
+                        }
+                }
             }
-        }
+        });
     }
 
     // partial[bh][split][matrix][d][e]
@@ -220,6 +244,173 @@ __global__ __launch_bounds__(NT, 2) void commit_partial_kernel(CommitArgs a)
                     part[(size_t)d * D + e] = acc[m][i][r];
                 }
         }
+    }
+}
+
+// Plain commit, producer / consumer form of the kernel above.  Staging a tile (row norms, scaling, hi/lo
+// split: vector ALU) and contracting it (MFMA) take about the same time, and a wavefront does not overlap
+// its own VALU work with its own MFMAs: wavefronts 0..3 (one per SIMD) only fetch and stage tile i + 1 into
+// the other LDS stage while wavefronts 4..7 (one per SIMD) only run the MFMAs of tile i, each on a 64 x 64
+// block of the partial; one workgroup barrier per tile hands the stages over.
+template <int D>
+__global__ __launch_bounds__(NT, 2) void commit_partial_ws_kernel(CommitArgs a)
+{
+    using C = CommitCfg<D, false>;
+    constexpr int PT = NT / 2;                           // producer threads
+    constexpr int KCHP = BT * C::CPR / PT;               // chunks per producer thread per tile (K and V each)
+    constexpr int RPP = PT / C::CPR;                     // rows per pass of the producers
+    constexpr int NE = D / 64;                           // 32-column blocks per consumer wavefront
+    static_assert(KCHP >= 1 && NE >= 1, "unsupported head dimension");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hh = lane >> 5;
+    const bool producer = wave < 4;
+    const int split = blockIdx.x % a.nsplit;
+    const int bh = blockIdx.x / a.nsplit;
+    const int h = bh % a.H, b = bh / a.H;
+    const int L = a.L, H = a.H;
+    const uint32_t tok_bytes = (uint32_t)H * D * 2;
+    const bf16_t *kg = (const bf16_t *)a.k + ((size_t)b * L * H + h) * D;
+    const bf16_t *vg = (const bf16_t *)a.v + ((size_t)b * L * H + h) * D;
+    const uint32_t range = (uint32_t)(L - 1) * tok_bytes + 2 * D;      // bytes of this head's slice
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(kg, range);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(vg, range);
+
+    const int ntiles = (L + BT - 1) / BT;
+    const int t_begin = (int)((long long)split * ntiles / a.nsplit);
+    const int t_end = (int)((long long)(split + 1) * ntiles / a.nsplit);
+    const int n = t_end - t_begin;
+
+    // ---- producers: chunk i of a thread is row (tid / CPR) + RPP * i, 16-byte column tid % CPR
+    const int lds_off = (tid / C::CPR) * C::ROW + 16 * (tid % C::CPR);
+    u32x4 kr[PFW][KCHP], vr[PFW][KCHP];
+    auto load_tile = [&](int tile, auto buf_) {     // a tile that is not this workgroup's is not requested
+        constexpr int buf = decltype(buf_)::value;
+        const uint32_t base = tile < t_end ? ((uint32_t)tile * BT + tid / C::CPR) * tok_bytes + 16 * (tid % C::CPR) : 0x80000000u;
+#pragma unroll
+        for (int i = 0; i < KCHP; ++i) {
+            const uint32_t off = base + (uint32_t)i * RPP * tok_bytes;
+            kr[buf][i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
+            vr[buf][i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
+        }
+    };
+    auto stage_tile = [&](int stage, auto buf_) {   // K as it is, and r * V split into bf16 hi + lo
+        constexpr int buf = decltype(buf_)::value;
+        unsigned char *sm = smem + stage * C::STAGE + lds_off;
+#pragma unroll
+        for (int i = 0; i < KCHP; ++i) {
+            float ss = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float lo = __uint_as_float(kr[buf][i][w] << 16);
+                const float hi = __uint_as_float(kr[buf][i][w] & 0xffff0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
+            }
+            ss = lane_group_sum<C::CPR>(ss);
+            const float rn = fast_rsqrt(ss + a.l2_eps);
+            // r * v as bf16 hi (truncated) + lo (rounded remainder): both members of a pair packed into one word
+            u32x4 vh, vl;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                uint32_t h0, h1;
+                float l0, l1;
+                split_bf16_trunc(__uint_as_float(vr[buf][i][w] << 16) * rn, h0, l0);
+                split_bf16_trunc(__uint_as_float(vr[buf][i][w] & 0xffff0000u) * rn, h1, l1);
+                vh[w] = (h0 >> 16) | h1;
+                union { bf16x2 v; uint32_t u; } pk;
+                pk.v[0] = to_bf16(l0);
+                pk.v[1] = to_bf16(l1);
+                vl[w] = pk.u;
+            }
+            unsigned char *p = sm + i * RPP * C::ROW;
+            *(u32x4 *)(p) = kr[buf][i];
+            *(u32x4 *)(p + C::MAT) = vh;
+            *(u32x4 *)(p + 2 * C::MAT) = vl;
+        }
+    };
+
+    // ---- consumers: wavefront 4 + cw owns rows 64 dh .. 64 dh + 63, column blocks e0 .. e0 + NE - 1
+    const int cw = wave - 4;
+    const bool consumer = !producer && cw * NE < C::DH * C::EB;
+    const int dh = (cw * NE) / C::EB, e0 = (cw * NE) % C::EB;
+    const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    f32x16 acc[2][NE];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][e][r] = 0.f;
+    auto consume = [&](int stage) {
+        const unsigned char *sm = smem + stage * C::STAGE + tr_off;
+        // operand fragments of 16-token step t: tokens 16t + 4hh + 0..3 and 16t + 8 + 4hh + 0..3
+        bf16x8 ka[2][2], bh_[2][NE], bl_[2][NE];
+        auto load_step = [&](int t, int buf) {
+            const unsigned char *row = sm + 16 * t * C::ROW;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) ka[buf][i] = lds_read_tr_pair(row + 64 * (2 * dh + i), 8 * C::ROW);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                bh_[buf][e] = lds_read_tr_pair(row + C::MAT + 64 * (e0 + e), 8 * C::ROW);
+                bl_[buf][e] = lds_read_tr_pair(row + 2 * C::MAT + 64 * (e0 + e), 8 * C::ROW);
+            }
+        };
+        load_step(0, 0);
+#pragma unroll
+        for (int t = 0; t < BT / 16; ++t) {
+            if (t + 1 < BT / 16) load_step(t + 1, (t + 1) & 1);
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    acc[i][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bh_[t & 1][e], acc[i][e], 0, 0, 0);
+                    acc[i][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t & 1][i], bl_[t & 1][e], acc[i][e], 0, 0, 0);
+                }
+        }
+    };
+
+    // tile k of this workgroup (k = 0 .. n - 1) travels through register buffer k % PFW and LDS stage k % 2
+    if (producer) {
+        static_for<0, PFW>([&](auto i_) { load_tile(t_begin + decltype(i_)::value, i_); });
+        if (n > 0) {
+            stage_tile(0, std::integral_constant<int, 0>{});
+            load_tile(t_begin + PFW, std::integral_constant<int, 0>{});
+        }
+    }
+    __syncthreads();
+    for (int i0 = 0; i0 < n; i0 += PFW) {
+        static_for<0, PFW>([&](auto j_) {
+            constexpr int j = decltype(j_)::value;
+            const int i = i0 + j;
+            if (i >= n) return;                          // uniform over the workgroup
+            if (producer) {
+                if (i + 1 < n) {
+                    const std::integral_constant<int, (j + 1) % PFW> nb{};
+                    stage_tile((i + 1) & 1, nb);
+                    load_tile(t_begin + i + 1 + PFW, nb);
+                }
+            } else if (consumer) {
+                consume(i & 1);
+            }
+            __syncthreads();
+        });
+    }
+
+    // partial[bh][split][d][e]
+    if (consumer) {
+        float *part = (float *)a.workspace + ((size_t)bh * a.nsplit + split) * D * D;
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int d = 32 * (2 * dh + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int col = 32 * (e0 + e) + (lane & 31);
+                    part[(size_t)d * D + col] = acc[i][e][r];
+                }
     }
 }
 
@@ -313,9 +504,9 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
     if ((long long)(a.L + 4 * BT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool delta = a.beta != nullptr;
     if (a.D == 128 && !delta)
-        hipLaunchKernelGGL((commit_partial_kernel<128, false>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL(commit_partial_ws_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else if (a.D == 64 && !delta)
-        hipLaunchKernelGGL((commit_partial_kernel<64, false>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL(commit_partial_ws_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else if (a.D == 128)
         hipLaunchKernelGGL((commit_partial_kernel<128, true>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
     else if (a.D == 64)

@@ -99,6 +99,37 @@ __device__ __forceinline__ float xhalf_max(float x)
     return fmaxf(x, __shfl_xor(x, 32, kWave));
 }
 
+// Sum over aligned groups of N = 8 or 16 consecutive lanes, every lane of the group receiving it, in
+// data-parallel-primitive adds (no LDS crossbar): pairs and quads by quad permutation, then the other
+// quad of the 8 (row_half_mirror) and the other half of the 16 (row_mirror), whose lanes already agree.
+template <int CTRL>
+__device__ __forceinline__ float dpp_peek(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+template <int N>
+__device__ __forceinline__ float lane_group_sum(float x)
+{
+    static_assert(N == 8 || N == 16, "groups of 8 or 16 lanes");
+    x += dpp_peek<0xB1>(x);                  // quad_perm [1,0,3,2]
+    x += dpp_peek<0x4E>(x);                  // quad_perm [2,3,0,1]
+    x += dpp_peek<0x141>(x);                 // row_half_mirror
+    if constexpr (N == 16) x += dpp_peek<0x140>(x);   // row_mirror
+    return x;
+}
+
+// 1 / sqrt(x) in one hardware instruction (about 1 ulp); x > 0.
+__device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+
+// x as the sum of two bf16 values: hi is x truncated to bf16 (exact bit mask), lo the rounded remainder;
+// the remainder of a truncation has at most 16 significant bits, so hi + lo misses x by 2^-16 |x| at most.
+// Returns hi and lo as the upper halves of two 32-bit words (bf16 bit patterns).
+__device__ __forceinline__ void split_bf16_trunc(float x, uint32_t &hi_bits, float &lo)
+{
+    hi_bits = __float_as_uint(x) & 0xffff0000u;
+    lo = x - __uint_as_float(hi_bits);
+}
+
 // Round-to-nearest-even fp32 -> bf16 (hardware conversion on gfx950).
 __device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)x; }
 

@@ -137,9 +137,8 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
                 ss = fmaf(lo, lo, ss);
                 ss = fmaf(hi, hi, ss);
             }
-#pragma unroll
-            for (int o = 1; o < C::CPR; o <<= 1) ss += __shfl_xor(ss, o, kWave);
-            if (col == 0) sc_r[row] = 1.0f / sqrtf(ss + a.l2_eps);
+            ss = lane_group_sum<C::CPR>(ss);
+            if (col == 0) sc_r[row] = fast_rsqrt(ss + a.l2_eps);
             *(u32x4 *)(R0 + row * C::ROW + 16 * col) = kr;
             *(u32x4 *)(R1 + row * C::ROW + 16 * col) = vr;
         }
