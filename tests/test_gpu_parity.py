@@ -439,6 +439,21 @@ def test_gdn_commit_full_size(lib, oracle):
     assert torch.equal(S_dev, S2)
 
 
+def test_gdn_commit_batched_full_size(lib, oracle):
+    """8 streams at the headline shape (96 heads: more scan workgroups than one round of CUs)."""
+    w = W.WORKLOADS["wan_batched"]
+    k, v, _ = W.clean_inputs(w, 0)
+    alpha, beta = W.token_gates(w, 0)
+    S0 = W.normal(17, w, (w.B, w.H, w.D, w.D), 0, 0, 99, io_dtype="f32") * 0.2
+    S_dev = dev(S0).clone()
+    lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, _gdn_ws(lib, w))
+    torch.cuda.synchronize()
+    S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), to_np(S0).astype(np.float64))
+    e = rel_err_per_head(to_np(S_dev), S_ref)
+    print(f"[wan_batched] token-sequential commit: state err {e:.3e}", flush=True)
+    assert e <= TOL_STATE
+
+
 # ---------------------------------------------------------------- feature maps of Eq. (3), the linear branch's own query
 
 def _bf16_round(x64):
