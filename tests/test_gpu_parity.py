@@ -607,3 +607,51 @@ def test_gate_projection_feeds_the_readout_full_size(lib, oracle):
     ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S0).astype(np.float64), g_ref.astype(np.float32), rows=rows)
     e = rel_err(to_np(out)[:, rows], ref)
     assert e <= TOL_BF16_OUT, f"{e:.3e}"
+
+
+# ---------------------------------------------------------------- stream capture
+
+def test_chunk_step_replays_from_a_captured_graph(lib):
+    """The library neither allocates nor synchronises, so a whole chunk step (readout passes, feature map,
+    gate projection, all three commit rules) can be captured into a graph.  Every replay must reproduce the
+    eager result bit for bit, with eager work and synchronisations between the replays."""
+    w = W.WORKLOADS["ragged_small"]
+    q, k, v, g = (dev(t) for t in W.pass_inputs(w, 0, 0))
+    kc, vc, gate = (dev(t) for t in W.clean_inputs(w, 0))
+    alpha, beta_t = (dev(t) for t in W.token_gates(w, 0))
+    beta = torch.full((w.B, w.H), 0.1, device="cuda")
+    Wq, _, _ = (dev(t) for t in W.feature_weights(w))
+    cs, sn = (dev(t) for t in W.rope_tables(w))
+    xh, Wg = (dev(t) for t in W.gate_inputs(w, 0, 0))
+    S0 = dev(W.normal(18, w, (w.B, w.H, w.D, w.D), 0, 0, 100, io_dtype="f32")) * 0.2
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    ws_gdn = _gdn_ws(lib, w)
+    S = S0.clone()
+    out, ql, gg = torch.empty_like(q), torch.empty_like(q), torch.empty_like(g)
+
+    def step():
+        lib.arl2_gate_proj(xh, Wg, gg)
+        lib.arl2_feature_map(q, Wq, cs, sn, ql)
+        lib.arl2_hybrid_attn_fwd_ex(q, k, v, ql, S, gg, out)
+        lib.arl2_state_commit(kc, vc, gate, S, ws)
+        lib.arl2_state_commit_delta(kc, vc, gate, beta, S, ws)
+        lib.arl2_state_commit_gdn(kc, vc, alpha, beta_t, S, ws_gdn)
+
+    step()                                               # eager reference: one step from S0
+    torch.cuda.synchronize()
+    out_ref, S_ref = out.clone(), S.clone()
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    S.copy_(S0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for _ in range(3):
+        S.copy_(S0)                                      # eager work between the replays
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, out_ref) and torch.equal(S, S_ref)
