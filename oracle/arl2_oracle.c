@@ -50,7 +50,10 @@ static void fwd_row_f64(int H, int Lkv, int D,
                         const float *k_bh,             /* k[b][0][h][:], stride H*D  */
                         const float *v_bh,             /* v[b][0][h][:], stride H*D  */
                         const double *S_bh,            /* S[b][h] or NULL            */
-                        double g_i, double sm_scale, double l2_eps,
+                        double g_i,                    /* headwise gate of this row, Eq. (6) */
+                        const float *g_vec,            /* or one gate per output feature (the element-wise
+                                                          granularity of the gate ablation); NULL: g_i */
+                        double sm_scale, double l2_eps,
                         double *score,                 /* scratch, Lkv               */
                         double *out_row)               /* D                          */
 {
@@ -90,7 +93,7 @@ static void fwd_row_f64(int H, int Lkv, int D,
             double o = 0.0;
             for (int d = 0; d < D; ++d)
                 o += ((double)ql_row[d] / nq) * S_bh[(size_t)d * D + e];
-            out_row[e] += g_i * o;
+            out_row[e] += (g_vec ? (double)g_vec[e] : g_i) * o;
         }
     }
 }
@@ -103,7 +106,7 @@ static void fwd_row_f64(int H, int Lkv, int D,
  */
 int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                      const float *q, const float *k, const float *v, const float *q_lin,
-                     const double *S, const float *g,
+                     const double *S, const float *g, int g_per_element,
                      double sm_scale, double l2_eps,
                      const int32_t *rows, int nrows,
                      double *out);
@@ -115,17 +118,19 @@ int arl2o_fwd_f64(int B, int H, int Lq, int Lkv, int D,
                   const int32_t *rows, int nrows,
                   double *out)
 {
-    return arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, q, k, v, NULL, S, g, sm_scale, l2_eps, rows, nrows, out);
+    return arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, q, k, v, NULL, S, g, 0, sm_scale, l2_eps, rows, nrows, out);
 }
 
 /*
  * The same pass with the inter branch's query given apart: q_lin [B][Lq][H][D] holds RoPE(phi_q(Q))
  * of Eq. (3), which the inter branch normalises and multiplies with S (Eq. (5)), while the intra
  * branch keeps q (Eq. (2)).  q_lin == NULL: the inter branch normalises q itself.
+ * g_per_element != 0: g is [B][Lq][H][D], one gate per output feature (the element-wise gate of the
+ * paper's gate-granularity ablation) instead of the headwise [B][Lq][H] of Eq. (6).
  */
 int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                      const float *q, const float *k, const float *v, const float *q_lin,
-                     const double *S, const float *g,
+                     const double *S, const float *g, int g_per_element,
                      double sm_scale, double l2_eps,
                      const int32_t *rows, int nrows,
                      double *out)
@@ -151,10 +156,12 @@ int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                 const float *k_bh = k + ((size_t)b * Lkv * H + h) * D;
                 const float *v_bh = v + ((size_t)b * Lkv * H + h) * D;
                 const double *S_bh = S ? S + ((size_t)b * H + h) * D * D : NULL;
-                const double g_i = g ? (double)g[((size_t)b * Lq + i) * H + h] : 1.0;
+                const size_t gi = ((size_t)b * Lq + i) * H + h;
+                const double g_i = (g && !g_per_element) ? (double)g[gi] : 1.0;
+                const float *g_vec = (g && g_per_element) ? g + gi * D : NULL;
                 double *out_row = out + (((size_t)b * nrows + r) * H + h) * D;
                 const float *ql_row = q_lin ? q_lin + (((size_t)b * Lq + i) * H + h) * D : q_row;
-                fwd_row_f64(H, Lkv, D, q_row, ql_row, k_bh, v_bh, S_bh, g_i, sm_scale, l2_eps,
+                fwd_row_f64(H, Lkv, D, q_row, ql_row, k_bh, v_bh, S_bh, g_i, g_vec, sm_scale, l2_eps,
                             score, out_row);
             }
         }

@@ -52,7 +52,7 @@ def _load():
         lib.arl2o_commit_f32.restype = i32
         lib.arl2o_commit_delta_f64.argtypes = [i32] * 4 + [vp] * 4 + [f64, vp]
         lib.arl2o_commit_delta_f64.restype = i32
-        lib.arl2o_fwd_ex_f64.argtypes = [i32] * 5 + [vp] * 6 + [f64, f64, vp, i32, vp]
+        lib.arl2o_fwd_ex_f64.argtypes = [i32] * 5 + [vp] * 6 + [i32, f64, f64, vp, i32, vp]
         lib.arl2o_fwd_ex_f64.restype = i32
         lib.arl2o_feature_map_f64.argtypes = [i32] * 4 + [vp] * 5
         lib.arl2o_feature_map_f64.restype = i32
@@ -96,7 +96,8 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
     """Readout pass: out = softmax(q k^T * sm_scale) v + g * L2Norm(q) S   (Eq. 2, 3, 5, 6).
 
     ``q_lin`` (fp64 path only), if given, is the row the inter branch normalises instead of q:
-    RoPE(phi_q(Q)) of Eq. (3).
+    RoPE(phi_q(Q)) of Eq. (3).  A 4-dimensional ``g`` [B, Lq, H, D] (fp64 path only) is one gate per
+    output feature, the element-wise granularity of the paper's gate ablation.
 
     ``rows`` restricts the computation to those query indices (each output row
     depends only on its own q row and on all of k, v, S); the result is then
@@ -107,7 +108,10 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
     g = None if g is None else _c(g, np.float32)
     st = np.float64 if precision == "f64" else np.float32
     S = None if S is None else _c(S, st)
-    B, H, Lq, Lkv, D = _check_shapes(q, k, v, S, g)
+    g_elem = g is not None and g.ndim == 4
+    if g_elem and g.shape != q.shape:
+        raise ValueError("an element-wise gate must have the shape of q")
+    B, H, Lq, Lkv, D = _check_shapes(q, k, v, S, None if g_elem else g)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(D)  # Eq. (1)
     if rows is None:
@@ -118,14 +122,15 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
         if nrows and (rows_arr.min() < 0 or rows_arr.max() >= Lq):
             raise ValueError("row index out of range")
     out = np.empty((B, nrows, H, D), dtype=st)
-    if q_lin is not None:
+    if q_lin is not None or g_elem:
         if precision != "f64":
-            raise ValueError("q_lin is supported by the fp64 oracle only")
-        q_lin = _c(q_lin, np.float32)
-        if q_lin.shape != q.shape:
-            raise ValueError("q_lin must have the shape of q")
+            raise ValueError("q_lin and element-wise gates are supported by the fp64 oracle only")
+        if q_lin is not None:
+            q_lin = _c(q_lin, np.float32)
+            if q_lin.shape != q.shape:
+                raise ValueError("q_lin must have the shape of q")
         rc = lib.arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, _ptr(q), _ptr(k), _ptr(v), _ptr(q_lin), _ptr(S), _ptr(g),
-                                  float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
+                                  int(g_elem), float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
         if rc != 0:
             raise MemoryError("oracle fwd failed")
         return out

@@ -556,3 +556,26 @@ def test_gate_proj_pins(oracle):
     xh = np.array([[[1.0, 2.0]]], dtype=np.float32)
     wh = np.array([[math.log(3.0), 0.0], [0.0, -math.log(3.0) / 2.0]], dtype=np.float32)
     np.testing.assert_allclose(oracle.gate_proj(xh, wh)[0, 0], [0.75, 0.25], rtol=1e-7)
+
+
+def test_gate_granularities(oracle):
+    """Eq. (6)'s gate is one value per (token, head).  The two other granularities of the paper's gate
+    ablation: one value per token (the same [B, L, H] array with equal entries per head) and one value per
+    output feature ([B, L, H, D], multiplying the linear branch element by element)."""
+    B, L, H, D = 1, 7, 3, 8
+    q, k, v = rand(B, L, H, D), rand(B, L, H, D), rand(B, L, H, D)
+    S = rng.standard_normal((B, H, D, D))
+    g = rng.uniform(0.2, 0.8, (B, L, H)).astype(np.float32)
+    base = oracle.fwd(q, k, v, S, g)
+    # an element-wise gate that is constant over the features is the headwise gate
+    ge = np.repeat(g[..., None], D, axis=-1)
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, S, ge), base)
+    # in general: out = intra + g (.) inter, element by element
+    ge = rng.uniform(0.0, 1.0, (B, L, H, D)).astype(np.float32)
+    intra = oracle.fwd(q, k, v, None, None)
+    inter = oracle.fwd(q, k, v, S, None) - intra
+    np.testing.assert_allclose(oracle.fwd(q, k, v, S, ge), intra + ge.astype(np.float64) * inter, rtol=1e-12, atol=1e-13)
+    # a per-token gate is the headwise array with the token's value repeated for every head
+    gt = rng.uniform(0.2, 0.8, (B, L, 1)).astype(np.float32)
+    got = oracle.fwd(q, k, v, S, np.repeat(gt, H, axis=2))
+    np.testing.assert_allclose(got, intra + gt[..., None].astype(np.float64) * inter, rtol=1e-12, atol=1e-13)
