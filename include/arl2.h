@@ -60,6 +60,11 @@ typedef enum {
 
 typedef enum { ARL2_F32 = 0, ARL2_BF16 = 1 } arl2_dtype;
 
+/* Granularity of the branch-mix gate g of the readout pass.  The paper's gate is headwise (Eq. (6));
+ * its gate ablation also has one gate per token (pass the headwise array with equal entries per head)
+ * and one gate per output feature (ARL2_GATE_PER_ELEMENT, g of shape [B][Lq][H][D], 16-byte aligned). */
+typedef enum { ARL2_GATE_PER_HEAD = 0, ARL2_GATE_PER_ELEMENT = 1 } arl2_gate_mode;
+
 typedef struct {
     int32_t B;            /* independent streams, >= 1                                      */
     int32_t H;            /* heads, >= 1                                                    */
@@ -71,6 +76,7 @@ typedef struct {
     int32_t g_dtype;      /* arl2_dtype of g (ignored when g == NULL)                       */
     float sm_scale;       /* softmax logit scale; 0 selects 1/sqrt(D)   (Eq. (1))           */
     float l2_eps;         /* epsilon inside L2Norm's square root; 0 selects 1e-6            */
+    int32_t g_mode;       /* arl2_gate_mode of g; 0 (zero-initialised descriptor) is headwise */
     void *workspace;      /* device scratch for arl2_state_commit, >= arl2_workspace_bytes  */
     size_t workspace_bytes;
     void *stream;         /* hipStream_t; NULL is the default stream                        */

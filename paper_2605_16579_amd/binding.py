@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libarl2_hip.so")
 
 ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ERR_DEVICE = range(5)
 ARL2_F32, ARL2_BF16 = 0, 1
+ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT = 0, 1
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
            "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_feature_map", "arl2_gate_proj",
@@ -27,7 +28,7 @@ class arl2_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Lq", ctypes.c_int32),
                 ("Lkv", ctypes.c_int32), ("D", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
                 ("g_dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float), ("l2_eps", ctypes.c_float),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("g_mode", ctypes.c_int32), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
 
 
@@ -113,6 +114,7 @@ def make_desc(B, H, Lq, Lkv, D, io_dtype, g_dtype=ARL2_F32, sm_scale=0.0, l2_eps
     d.B, d.H, d.Lq, d.Lkv, d.D = B, H, Lq, Lkv, D
     d.io_dtype, d.g_dtype = io_dtype, g_dtype
     d.sm_scale, d.l2_eps = sm_scale, l2_eps
+    d.g_mode = ARL2_GATE_PER_HEAD
     if workspace is not None:
         d.workspace = _dev(workspace, "workspace")
         d.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -142,10 +144,13 @@ def arl2_hybrid_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     io = _dtype_code(q)
     d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
                   stream=stream)
+    g_shape = (B, Lq, H)
+    if g is not None and g.dim() == 4:                    # one gate per output feature
+        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
     st = load_library().arl2_hybrid_attn_fwd(
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
-        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", (B, Lq, H)),
+        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", g_shape),
         _dev(out, "out", (B, Lq, H, D), q.dtype))
     _check(st)
 
@@ -161,11 +166,14 @@ def arl2_hybrid_attn_fwd_ex(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q
     io = _dtype_code(q)
     d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
                   stream=stream)
+    g_shape = (B, Lq, H)
+    if g is not None and g.dim() == 4:                    # one gate per output feature
+        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
     st = load_library().arl2_hybrid_attn_fwd_ex(
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
         _dev(q_lin, "q_lin", (B, Lq, H, D), q.dtype),
-        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", (B, Lq, H)),
+        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", g_shape),
         _dev(out, "out", (B, Lq, H, D), q.dtype))
     _check(st)
 

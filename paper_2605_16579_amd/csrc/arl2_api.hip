@@ -28,6 +28,8 @@ arl2_status check_desc(const arl2_desc *d)
         return fail(ARL2_ERR_INVALID_ARG, "io_dtype is not an arl2_dtype");
     if (d->g_dtype != ARL2_F32 && d->g_dtype != ARL2_BF16)
         return fail(ARL2_ERR_INVALID_ARG, "g_dtype is not an arl2_dtype");
+    if (d->g_mode != ARL2_GATE_PER_HEAD && d->g_mode != ARL2_GATE_PER_ELEMENT)
+        return fail(ARL2_ERR_INVALID_ARG, "g_mode is not an arl2_gate_mode");
     if (d->D != 64 && d->D != 128) return fail(ARL2_ERR_UNSUPPORTED, "D must be 64 or 128");
     if (!(d->sm_scale >= 0.f) || !(d->l2_eps >= 0.f))
         return fail(ARL2_ERR_INVALID_ARG, "sm_scale and l2_eps must be >= 0 (0 selects the default)");
@@ -67,6 +69,8 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
         return fail(ARL2_ERR_INVALID_ARG, "q, k, v, q_lin, S and out must be 16-byte aligned");
     if (g && (reinterpret_cast<uintptr_t>(g) & 3u))
         return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
+    if (g && desc->g_mode == ARL2_GATE_PER_ELEMENT && !aligned16(g))
+        return fail(ARL2_ERR_INVALID_ARG, "an element-wise g must be 16-byte aligned");
     if (out == q || out == k || out == v || out == q_lin)
         return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
     if (S != nullptr && desc->Lkv != desc->Lq)
@@ -77,6 +81,7 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
     a.q_lin = (S != nullptr) ? q_lin : nullptr;
     a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
+    a.g_per_element = desc->g_mode == ARL2_GATE_PER_ELEMENT;
     a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
     a.l2_eps = resolved_eps(desc);
     hipStream_t stream = reinterpret_cast<hipStream_t>(desc->stream);

@@ -31,6 +31,7 @@ struct FwdArgs {
     void *out;
     int B, H, Lq, Lkv, D;
     int g_is_bf16;
+    int g_per_element;     // g is [B][Lq][H][D] instead of [B][Lq][H]
     float sm_scale;        // already resolved (never 0)
     float l2_eps;          // already resolved
 };

@@ -94,13 +94,16 @@ __global__ __launch_bounds__(NT) void fwd_f32_kernel(FwdArgs a)
                 for (int e = 0; e < EPL; ++e) oi[e] = fmaf(qd, Sg[(size_t)d * D + e], oi[e]);
             }
         }
-        float g = 1.0f;
-        if (a.g != nullptr) {
-            const size_t gi = ((size_t)b * Lq + rowc) * H + h;
-            g = a.g_is_bf16 ? (float)((const bf16_t *)a.g)[gi] : ((const float *)a.g)[gi];
-        }
+        const size_t gi = ((size_t)b * Lq + rowc) * H + h;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) o[i] = fmaf(g, oi[i], o[i]);
+        for (int i = 0; i < EPL; ++i) {
+            float g = 1.0f;                  // headwise gate, or one gate per output feature
+            if (a.g != nullptr) {
+                const size_t ge = a.g_per_element ? gi * D + sub * EPL + i : gi;
+                g = a.g_is_bf16 ? (float)((const bf16_t *)a.g)[ge] : ((const float *)a.g)[ge];
+            }
+            o[i] = fmaf(g, oi[i], o[i]);
+        }
     }
     if (valid) {
         float *og = (float *)a.out + (((size_t)b * Lq + row) * H + h) * D + sub * EPL;

@@ -400,14 +400,36 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
             }
         // gate * L2 norm scale for this lane's query row
         float gq = 1.0f / sqrtf(qss + a.l2_eps);
-        if (a.g != nullptr && qrow < Lq) {
-            const size_t gi = ((size_t)b * Lq + qrow) * H + h;
+        const size_t gi = ((size_t)b * Lq + (qrow < Lq ? qrow : 0)) * H + h;
+        if (a.g != nullptr && !a.g_per_element && qrow < Lq)
             gq *= a.g_is_bf16 ? (float)((const bf16_t *)a.g)[gi] : ((const float *)a.g)[gi];
+        if (a.g != nullptr && a.g_per_element) {
+            // one gate per output feature: registers 4 j .. 4 j + 3 of block db are features 32 db + 8 j + 4 hh + 0..3
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const size_t ge = gi * D + 32 * db + 8 * j + 4 * hh;
+                    float g4[4];
+                    if (a.g_is_bf16) {
+                        const bf16x4 x = *(const bf16x4 *)((const bf16_t *)a.g + ge);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) g4[i] = (float)x[i];
+                    } else {
+                        const f32x4 x = *(const f32x4 *)((const float *)a.g + ge);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) g4[i] = x[i];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        o_acc[db][4 * j + i] = fmaf(gq * g4[i], inter[db][4 * j + i], o_acc[db][4 * j + i]);
+                }
+        } else {
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] = fmaf(gq, inter[db][r], o_acc[db][r]);
         }
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[db][r] = fmaf(gq, inter[db][r], o_acc[db][r]);
     }
 
     // transpose through LDS so that every output row is written as contiguous 16-byte pieces

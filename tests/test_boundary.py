@@ -122,6 +122,11 @@ def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
     assert fm(d, y=0x1000) == 1                           # in place
     df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
     assert fm(df) == 2
+    dg = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    dg.g_mode = 7
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x1000, 0x2000, 0x3000, 0x4000, 0x7000, 0x5000) == 1   # not a gate mode
+    dg.g_mode = A.ARL2_GATE_PER_ELEMENT
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x1000, 0x2000, 0x3000, 0x4000, 0x7004, 0x5000) == 1   # element-wise g: 16-byte aligned
     ex = lambda d, ql=0x6000, out=0x5000: lib.arl2_hybrid_attn_fwd_ex(ctypes.byref(d), 0x1000, 0x2000, 0x3000, ql, 0x4000, None, out)
     assert ex(d, ql=0x6008) == 1                          # misaligned q_lin
     assert ex(d, ql=0x5000) == 1                          # out aliases q_lin

@@ -609,6 +609,31 @@ def test_gate_projection_feeds_the_readout_full_size(lib, oracle):
     assert e <= TOL_BF16_OUT, f"{e:.3e}"
 
 
+@pytest.mark.parametrize("io,gdt", [("bf16", "f32"), ("bf16", "bf16"), ("f32", "f32")])
+def test_elementwise_gate(lib, oracle, io, gdt):
+    """One gate per output feature ([B, L, H, D]), the finest granularity of the paper's gate ablation."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="gate_elem_" + io, io_dtype=io, L=200 if io == "f32" else 328)
+    q, k, v, g_head = W.pass_inputs(w, 0, 0)
+    ge = W.uniform(19, w, (w.B, w.L, w.H, w.D), 0.0, 1.0, 0, 0, 101)
+    if gdt == "bf16":
+        ge = ge.to(torch.bfloat16)
+    S = W.normal(20, w, (w.B, w.H, w.D, w.D), 0, 0, 102, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(ge), out)
+    torch.cuda.synchronize()
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(ge))
+    e = rel_err(to_np(out), ref)
+    assert e <= (TOL_BF16_OUT if io == "bf16" else 1e-4), f"{io}/{gdt}: {e:.3e}"
+    # constant over the features it is the headwise gate, bit for bit
+    gc = g_head[..., None].expand(-1, -1, -1, w.D).contiguous()
+    o1, o2 = torch.empty_like(out), torch.empty_like(out)
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(gc), o1)
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(g_head), o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+
+
 # ---------------------------------------------------------------- stream capture
 
 def test_chunk_step_replays_from_a_captured_graph(lib):
