@@ -40,6 +40,10 @@ arl2_status check_desc(const arl2_desc *d)
     return ARL2_OK;
 }
 
+// The kernels address one stream's [L][H][D] slice (and the feature map / gate projection the whole
+// [B][L][H][D] array) with 32-bit byte offsets.
+bool fits_32bit(double elems, int elem_bytes) { return elems * elem_bytes <= 2147483647.0; }
+
 float resolved_eps(const arl2_desc *d) { return d->l2_eps > 0.f ? d->l2_eps : 1e-6f; }
 
 size_t commit_workspace(const arl2_desc *d)
@@ -75,6 +79,8 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
         return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
     if (S != nullptr && desc->Lkv != desc->Lq)
         return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
+    if (desc->io_dtype == ARL2_BF16 && !fits_32bit(((double)desc->Lkv + 256.0) * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
 
     arl2::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.S = S; a.g = (S != nullptr) ? g : nullptr; a.out = out;
@@ -111,6 +117,8 @@ arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W
         return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be 8-byte aligned");
     if (y == x || y == W) return fail(ARL2_ERR_INVALID_ARG, "y must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_feature_map takes bf16 x, W only");
+    if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
 
     arl2::FmapArgs a;
     a.x = x; a.W = W; a.cs = rope_cos; a.sn = rope_sin; a.y = y;
@@ -130,6 +138,8 @@ arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg,
     if (g == x || g == Wg) return fail(ARL2_ERR_INVALID_ARG, "g must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj takes bf16 x, Wg only");
     if (desc->H > 32) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj supports up to 32 heads");
+    if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
 
     arl2::GateArgs a;
     a.x = x; a.Wg = Wg; a.g = g;
@@ -154,6 +164,8 @@ static arl2_status commit_common(const arl2_desc *desc, const void *k, const voi
     if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in a state commit");
     if (delta && desc->io_dtype != ARL2_BF16)
         return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_delta takes bf16 k, v only");
+    if (desc->io_dtype == ARL2_BF16 && !fits_32bit(((double)desc->Lq + 256.0) * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
     const size_t need = commit_workspace(desc);
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
@@ -202,6 +214,8 @@ arl2_status arl2_state_commit_gdn(const arl2_desc *desc, const void *k, const vo
     if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in a state commit");
     if (desc->io_dtype != ARL2_BF16)
         return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_gdn takes bf16 k, v only");
+    if (!fits_32bit(((double)desc->Lq + 256.0) * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
     const size_t need = arl2::gdn_workspace_bytes(desc->B, desc->H, desc->Lq, desc->D);
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_gdn_workspace_bytes()");

@@ -143,6 +143,23 @@ def test_gate_proj_rejects_bad_arguments(A):
     assert gp(A.make_desc(1, 40, 64, 64, 64, A.ARL2_BF16, stream=0)) == 2      # more than 32 heads
 
 
+def test_sizes_beyond_the_kernels_addressing_are_refused(A):
+    """One stream's k, v (the whole x for the feature map and the gate projection) are addressed with
+    32-bit byte offsets: larger problems return ARL2_ERR_UNSUPPORTED instead of launching."""
+    lib = A.load_library()
+    big = A.make_desc(1, 64, 200000, 200000, 128, A.ARL2_BF16, stream=0)     # 3.3 GB per stream
+    big.workspace, big.workspace_bytes = 0x10000, 1 << 62
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(big), 0x1000, 0x2000, 0x3000, None, None, 0x5000) == 2
+    assert lib.arl2_state_commit(ctypes.byref(big), 0x1000, 0x2000, 0x3000, 0x4000) == 2
+    assert lib.arl2_state_commit_gdn(ctypes.byref(big), 0x1000, 0x2000, 0x3000, 0x6000, 0x4000) == 2
+    assert lib.arl2_feature_map(ctypes.byref(big), 0x1000, 0x2000, None, None, 0x5000) == 2
+    many = A.make_desc(64, 12, 32768, 32768, 128, A.ARL2_BF16, stream=0)     # each stream small, x as a whole 6.4 GB
+    assert lib.arl2_feature_map(ctypes.byref(many), 0x1000, 0x2000, None, None, 0x5000) == 2
+    assert lib.arl2_gate_proj(ctypes.byref(many), 0x1000, 0x2000, 0x3000) == 2
+    empty = A.make_desc(1, 2, 0, 0, 64, A.ARL2_BF16, stream=0)               # no tokens
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(empty), 0x1000, 0x2000, 0x3000, None, None, 0x5000) == 1
+
+
 def test_binding_refuses_host_tensors(A):
     import torch
     q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16)

@@ -634,6 +634,33 @@ def test_elementwise_gate(lib, oracle, io, gdt):
     assert torch.equal(o1, o2)
 
 
+def test_degenerate_rows(lib, oracle):
+    """All-zero query and key rows (L2Norm gives 0, not NaN), identical keys (uniform softmax), and a
+    state commit whose keys are all zero (only the gate acts)."""
+    w = W.WORKLOADS["ragged_small"]
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    q[:, 5] = 0
+    q[:, 100:110] = 0
+    k[:, 7] = 0
+    k[:, 200:] = k[:, 200:201]                            # a run of identical keys
+    S = W.normal(21, w, (w.B, w.H, w.D, w.D), 0, 0, 103, io_dtype="f32") * 0.2
+    out = gpu_fwd(lib, q, k, v, S, g)
+    assert torch.isfinite(out.float()).all()
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(g))
+    assert rel_err(to_np(out), ref) <= TOL_BF16_OUT
+    kz = torch.zeros_like(k)
+    _, _, gate = W.clean_inputs(w, 0)
+    S_dev = dev(S).clone()
+    gpu_commit(lib, kz, v, gate, S_dev)
+    np.testing.assert_allclose(to_np(S_dev), to_np(S) * to_np(gate)[..., None, None], rtol=1e-6, atol=1e-7)
+    alpha, beta = W.token_gates(w, 0)
+    S_dev = dev(S).clone()
+    lib.arl2_state_commit_gdn(dev(kz), dev(v), dev(alpha), dev(beta), S_dev, _gdn_ws(lib, w))
+    torch.cuda.synchronize()
+    want = to_np(S).astype(np.float64) * to_np(alpha).astype(np.float64).prod(axis=1)[..., None, None]
+    assert rel_err_per_head(to_np(S_dev), want) <= TOL_STATE
+
+
 # ---------------------------------------------------------------- stream capture
 
 def test_chunk_step_replays_from_a_captured_graph(lib):
