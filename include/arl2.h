@@ -32,6 +32,8 @@
  * contiguous in the layouts below.  The library never allocates, frees or
  * synchronises: every call validates its arguments on the host, enqueues its kernels
  * on desc->stream and returns.  A call that returns an error has launched nothing.
+ * The kernels address one stream's k, v (the whole x for arl2_feature_map and arl2_gate_proj) with
+ * 32-bit byte offsets: such an array must stay below 2 GiB, larger problems return ARL2_ERR_UNSUPPORTED.
  *
  * Layouts (row-major):
  *   q, out      [B][Lq ][H][D]   io_dtype
