@@ -185,6 +185,8 @@ def main() -> int:
                     help="put the learned per-head maps of Eq. (3) on the path: every readout pass first computes "
                          "q_lin = RoPE(phi_q(Q)) (arl2_feature_map) and reads the state with it; the commit is preceded by "
                          "RoPE(phi_k(K)) and phi_v(V) of the clean pass.  Not the headline configuration.")
+    ap.add_argument("--unfused-maps", action="store_true",
+                    help="with --feature-maps: compute q_lin with a separate arl2_feature_map launch instead of inside the readout")
     ap.add_argument("--gate-proj", action="store_true",
                     help="compute the mix gate of every readout pass on the path, G = sigmoid(x W_g) (arl2_gate_proj), "
                          "instead of taking it as an input.  Not the headline configuration.")
@@ -298,8 +300,11 @@ def main() -> int:
             if gp is not None:
                 A.arl2_gate_proj(gp[p % w.passes][0], gp[p % w.passes][1], g)
             if fm is not None:
-                A.arl2_feature_map(q, fm["Wq"], fm["cs"], fm["sn"], fm["ql"])
-                A.arl2_hybrid_attn_fwd_ex(q, k, v, fm["ql"], S, g, outs[p % w.passes])
+                if args.unfused_maps:
+                    A.arl2_feature_map(q, fm["Wq"], fm["cs"], fm["sn"], fm["ql"])
+                    A.arl2_hybrid_attn_fwd_ex(q, k, v, fm["ql"], S, g, outs[p % w.passes])
+                else:      # the query map fused into the readout kernel: no intermediate array, one launch
+                    A.arl2_hybrid_attn_fwd_fm(q, k, v, q, fm["Wq"], fm["cs"], fm["sn"], S, g, outs[p % w.passes])
             else:
                 A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p % w.passes])
         if events is not None:
@@ -341,7 +346,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "commit_rule": rule, "feature_maps": bool(args.feature_maps), "gate_proj": bool(args.gate_proj),
+                   "passes": w.passes, "commit_rule": rule, "feature_maps": ("fused query map" if not args.unfused_maps else "separate launches") if args.feature_maps else False, "gate_proj": bool(args.gate_proj),
                    "readouts_per_step": n_read, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,

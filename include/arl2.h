@@ -116,6 +116,23 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc,
                                     const float *S, const void *g, void *out);
 
 /*
+ * The readout pass with the query feature map of the linear branch fused in (paper Eq. (2), (3), (5),
+ * (6)): the inter branch reads L2Norm(RoPE(Wq[h] xq)), computed inside the kernel and never stored;
+ * equal to arl2_feature_map(xq, Wq, ...) followed by arl2_hybrid_attn_fwd_ex, without the intermediate
+ * array and the second launch.
+ *   q, k, v   as in arl2_hybrid_attn_fwd (the softmax branch's inputs), bf16 only.
+ *   xq        device bf16 [B][Lq][H][D]: the projection the feature map acts on (before RoPE).
+ *   Wq, rope_cos, rope_sin   as in arl2_feature_map.
+ *   S         device fp32 [B][H][D][D], READ-ONLY, must not be NULL (without a state there is no
+ *             linear branch: use arl2_hybrid_attn_fwd).
+ */
+arl2_status arl2_hybrid_attn_fwd_fm(const arl2_desc *desc,
+                                    const void *q, const void *k, const void *v,
+                                    const void *xq, const void *Wq,
+                                    const float *rope_cos, const float *rope_sin,
+                                    const float *S, const void *g, void *out);
+
+/*
  * Per-head feature map of the linear branch, paper Eq. (3) without its L2Norm (the readout and the
  * commits normalise the rows they are given):
  *     y[b][l][h][:] = RoPE_l( W[h] x[b][l][h][:] )

@@ -20,7 +20,7 @@ ARL2_F32, ARL2_BF16 = 0, 1
 ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT = 0, 1
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
-           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_feature_map", "arl2_gate_proj",
+           "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_hybrid_attn_fwd_fm", "arl2_feature_map", "arl2_gate_proj",
            "arl2_status_string", "arl2_last_error", "arl2_version"]
 
 
@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_state_commit_delta.restype = ctypes.c_int
         lib.arl2_hybrid_attn_fwd_ex.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         lib.arl2_hybrid_attn_fwd_ex.restype = ctypes.c_int
+        lib.arl2_hybrid_attn_fwd_fm.argtypes = [dp] + [vp] * 10
+        lib.arl2_hybrid_attn_fwd_fm.restype = ctypes.c_int
         lib.arl2_feature_map.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_feature_map.restype = ctypes.c_int
         lib.arl2_gate_proj.argtypes = [dp, vp, vp, vp]
@@ -173,6 +175,30 @@ def arl2_hybrid_attn_fwd_ex(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
         _dev(q_lin, "q_lin", (B, Lq, H, D), q.dtype),
+        _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", g_shape),
+        _dev(out, "out", (B, Lq, H, D), q.dtype))
+    _check(st)
+
+
+def arl2_hybrid_attn_fwd_fm(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, xq: torch.Tensor, Wq: torch.Tensor,
+                            rope_cos: Optional[torch.Tensor], rope_sin: Optional[torch.Tensor],
+                            S: torch.Tensor, g: Optional[torch.Tensor], out: torch.Tensor,
+                            *, sm_scale: float = 0.0, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """The readout pass with the linear branch's query feature map RoPE(Wq[h] xq) computed inside the kernel."""
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [B, L, H, D]")
+    B, Lq, H, D = q.shape
+    Lkv = k.shape[1]
+    d = make_desc(B, H, Lq, Lkv, D, _dtype_code(q), _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
+                  stream=stream)
+    g_shape = (B, Lq, H)
+    if g is not None and g.dim() == 4:
+        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
+    st = load_library().arl2_hybrid_attn_fwd_fm(
+        ctypes.byref(d),
+        _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
+        _dev(xq, "xq", (B, Lq, H, D), q.dtype), _dev(Wq, "Wq", (H, D, D), q.dtype),
+        _dev(rope_cos, "rope_cos", (Lq, D // 2), torch.float32), _dev(rope_sin, "rope_sin", (Lq, D // 2), torch.float32),
         _dev(S, "S", (B, H, D, D), torch.float32), _dev(g, "g", g_shape),
         _dev(out, "out", (B, Lq, H, D), q.dtype))
     _check(st)

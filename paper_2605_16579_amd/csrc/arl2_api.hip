@@ -85,6 +85,7 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
     arl2::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.S = S; a.g = (S != nullptr) ? g : nullptr; a.out = out;
     a.q_lin = (S != nullptr) ? q_lin : nullptr;
+    a.xq = nullptr; a.Wq = nullptr; a.cs = nullptr; a.sn = nullptr;
     a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     a.g_per_element = desc->g_mode == ARL2_GATE_PER_ELEMENT;
@@ -101,6 +102,43 @@ arl2_status arl2_hybrid_attn_fwd(const arl2_desc *desc, const void *q, const voi
                                  const float *S, const void *g, void *out)
 {
     return arl2_hybrid_attn_fwd_ex(desc, q, k, v, nullptr, S, g, out);
+}
+
+arl2_status arl2_hybrid_attn_fwd_fm(const arl2_desc *desc, const void *q, const void *k, const void *v,
+                                    const void *xq, const void *Wq, const float *rope_cos, const float *rope_sin,
+                                    const float *S, const void *g, void *out)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!q || !k || !v || !out || !xq || !Wq || !S)
+        return fail(ARL2_ERR_INVALID_ARG, "q, k, v, xq, Wq, S and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(S) || !aligned16(xq) || !aligned16(Wq))
+        return fail(ARL2_ERR_INVALID_ARG, "q, k, v, xq, Wq, S and out must be 16-byte aligned");
+    if ((rope_cos == nullptr) != (rope_sin == nullptr))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
+    if ((reinterpret_cast<uintptr_t>(rope_cos) & 7u) || (reinterpret_cast<uintptr_t>(rope_sin) & 7u))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be 8-byte aligned");
+    if (g && (reinterpret_cast<uintptr_t>(g) & 3u)) return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
+    if (g && desc->g_mode == ARL2_GATE_PER_ELEMENT && !aligned16(g))
+        return fail(ARL2_ERR_INVALID_ARG, "an element-wise g must be 16-byte aligned");
+    if (out == q || out == k || out == v || out == xq || out == Wq)
+        return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
+    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
+    if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_hybrid_attn_fwd_fm takes bf16 inputs only");
+    if (!fits_32bit(((double)desc->Lkv + 256.0) * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
+
+    arl2::FwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.S = S; a.g = g; a.out = out; a.q_lin = nullptr;
+    a.xq = xq; a.Wq = Wq; a.cs = rope_cos; a.sn = rope_sin;
+    a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
+    a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
+    a.g_per_element = desc->g_mode == ARL2_GATE_PER_ELEMENT;
+    a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
+    a.l2_eps = resolved_eps(desc);
+    const hipError_t e = arl2::launch_fwd_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "fwd launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
 }
 
 arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W,

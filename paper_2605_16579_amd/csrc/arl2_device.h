@@ -26,6 +26,10 @@ constexpr int kWave = 64;
 struct FwdArgs {
     const void *q, *k, *v;
     const void *q_lin;     // row the linear branch normalises; nullptr: q itself
+    // or, fused: q_lin = RoPE(Wq[h] xq) computed in the kernel (all nullptr when not used)
+    const void *xq;        // [B][Lq][H][D] bf16, the projection the feature map acts on
+    const void *Wq;        // [H][D][D] bf16, [head][out][in]
+    const float *cs, *sn;  // [Lq][D/2] rotation tables, or both nullptr
     const float *S;        // may be nullptr
     const void *g;         // may be nullptr
     void *out;

@@ -64,8 +64,16 @@ struct FwdCfg {
     static constexpr int ST_BYTES = 2 * SS_BYTES;
     static constexpr int SCH = (D * CPR + NT - 1) / NT;   // 8-float state pieces per thread
     static constexpr int OUT_BYTES = BM * KROW;  // output staging [q][e]
-    static constexpr int SMEM = (KV_BYTES > ST_BYTES ? (KV_BYTES > OUT_BYTES ? KV_BYTES : OUT_BYTES)
-                                                     : (ST_BYTES > OUT_BYTES ? ST_BYTES : OUT_BYTES));
+    // fused feature map: half of Wq[h] (D/2 rows) plus, per wavefront, the rotation tables of its 32 tokens
+    static constexpr int WH_BYTES = (D / 2) * KROW;
+    static constexpr int TST = D / 2 + 2;        // floats per staged table row (conflict-free 8-byte reads)
+    static constexpr int TAB_BYTES = 2 * 32 * TST * 4;
+    static constexpr int FM_BYTES = WH_BYTES + (NT / 64) * TAB_BYTES;
+    static constexpr int WCH = ((D / 2) * CPR + NT - 1) / NT;     // 16-byte chunks of the Wq half per thread
+    static constexpr int TCH = 32 * (D / 8) / 64;                 // 16-byte chunks of one table tile per lane
+    static constexpr int SMEM0 = (KV_BYTES > ST_BYTES ? (KV_BYTES > OUT_BYTES ? KV_BYTES : OUT_BYTES)
+                                                      : (ST_BYTES > OUT_BYTES ? ST_BYTES : OUT_BYTES));
+    static constexpr int SMEM = SMEM0 > FM_BYTES ? SMEM0 : FM_BYTES;
     static constexpr int KCH = BN * CPR / NT;    // 16-byte chunks per thread per tile (K and V each)
     static constexpr int ROWS_PER_PASS = NT / CPR;
     static constexpr int S_LEN = 2 * KS;         // MFMAs of one S^T chain (two 32-key blocks)
@@ -357,6 +365,88 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
             }
             qss = xhalf_sum(qss);
         }
+        // Fused feature map of the linear branch (Eq. (3)): q_lin^T[e][row] = sum_d Wq[e][d] xq[row][d], rotated
+        // pair by pair, is never stored: the accumulator registers, rounded to bf16, are the B fragments of
+        // the readout (k-slot j of half-wave hh is feature 16t + 8(j/4) + 4hh + j%4, as for P^T above).
+        // Wq[h] passes through LDS in two halves of D/2 output rows (whole rows in, fragments out) and every
+        // wavefront stages the rotation table rows of its 32 tokens in a region of its own: read straight
+        // from global memory, fragment by fragment, these operands cost ~13 us of cache-line requests.
+        const bool fused_map = a.xq != nullptr;
+        if (fused_map) {
+            const size_t row_off = ((size_t)(b * (size_t)Lq + (qrow < Lq ? qrow : 0)) * H + h) * D;
+            bf16x8 xf[C::KS];
+#pragma unroll
+            for (int t = 0; t < C::KS; ++t) {
+                bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (qrow < Lq) x = *(const bf16x8 *)((const bf16_t *)a.xq + row_off + 16 * t + 8 * hh);
+                xf[t] = x;
+            }
+            unsigned char *smW = smem;                                           // D/2 rows of Wq[h], KROW bytes each
+            float *cosT = (float *)(smem + C::WH_BYTES + wave * C::TAB_BYTES);   // this wavefront's [32][TST] tables
+            float *sinT = cosT + 32 * C::TST;
+            const bool rope = a.cs != nullptr;
+            qss = 0.f;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                __syncthreads();                      // the K/V ring (or the previous half of Wq) is no longer read
+#pragma unroll
+                for (int i = 0; i < C::WCH; ++i) {    // chunk id: row id / CPR of this half, 16-byte column id % CPR
+                    const int id = tid + NT * i;
+                    const int wr = id / C::CPR, wc = id % C::CPR;
+                    if (wr < D / 2)
+                        *(u32x4 *)(smW + wr * C::KROW + 16 * wc) =
+                            *(const u32x4 *)((const bf16_t *)a.Wq + ((size_t)h * D + half * (D / 2) + wr) * D + 8 * wc);
+                }
+                if (half == 0 && rope) {
+#pragma unroll
+                    for (int i = 0; i < C::TCH; ++i) {
+                        const int id = lane + 64 * i;
+                        const int tk = id / (D / 8), col = id % (D / 8);
+                        const int trow = q0 + tk < Lq ? q0 + tk : Lq - 1;
+                        const u32x4 cv = *(const u32x4 *)(a.cs + (size_t)trow * (D / 2) + 4 * col);
+                        const u32x4 sv = *(const u32x4 *)(a.sn + (size_t)trow * (D / 2) + 4 * col);
+                        u32x2 *cd = (u32x2 *)(cosT + tk * C::TST + 4 * col), *sd = (u32x2 *)(sinT + tk * C::TST + 4 * col);
+                        cd[0] = u32x2{cv[0], cv[1]};
+                        cd[1] = u32x2{cv[2], cv[3]};
+                        sd[0] = u32x2{sv[0], sv[1]};
+                        sd[1] = u32x2{sv[2], sv[3]};
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int e2 = 0; e2 < C::DB / 2; ++e2) {
+                    const int eb = half * (C::DB / 2) + e2;
+                    f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int t = 0; t < C::KS; ++t) {
+                        const bf16x8 wf = *(const bf16x8 *)(smW + (32 * e2 + c) * C::KROW + 32 * t + 16 * hh);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[t], acc, 0, 0, 0);
+                    }
+                    if (rope) {
+#pragma unroll
+                        for (int j4 = 0; j4 < 4; ++j4) {      // registers 4 j4 .. +3: features 32 eb + 8 j4 + 4 hh + 0..3
+                            const f32x2 c2 = *(const f32x2 *)(cosT + c * C::TST + 16 * eb + 4 * j4 + 2 * hh);
+                            const f32x2 s2 = *(const f32x2 *)(sinT + c * C::TST + 16 * eb + 4 * j4 + 2 * hh);
+#pragma unroll
+                            for (int p = 0; p < 2; ++p) {
+                                const float y0 = acc[4 * j4 + 2 * p], y1 = acc[4 * j4 + 2 * p + 1];
+                                acc[4 * j4 + 2 * p] = y0 * c2[p] - y1 * s2[p];
+                                acc[4 * j4 + 2 * p + 1] = fmaf(y0, s2[p], y1 * c2[p]);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const bf16_t y = to_bf16(acc[8 * tt + j]);
+                            qf[2 * eb + tt][j] = y;
+                            qss = fmaf((float)y, (float)y, qss);
+                        }
+                }
+            }
+            qss = xhalf_sum(qss);
+        }
         unsigned char *smHi = smem, *smLo = smem + C::SS_BYTES;
         __syncthreads();                              // every wave is done with the K/V ring
 #pragma unroll
@@ -385,15 +475,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         for (int db = 0; db < C::DB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) inter[db][r] = 0.f;
-        // k-slot j of half-wave hh must be d = 16t + 8hh + j to match the q fragments
-        const int s_frag_off = (8 * hh + ((lane & 15) >> 2)) * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+        // k-slot j of half-wave hh must be d = 16t + 8hh + j to match q fragments loaded from memory, and
+        // d = 16t + 8(j/4) + 4hh + j%4 to match fragments that were accumulator registers (fused feature map)
+        const int s_row = fused_map ? ((lane & 15) >> 2) + 4 * hh : 8 * hh + ((lane & 15) >> 2);
+        const int s_second = (fused_map ? 8 : 4) * C::VROW;
+        const int s_frag_off = s_row * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
 #pragma unroll
         for (int t = 0; t < C::KS; ++t)
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) {
                 const unsigned char *p = smHi + s_frag_off + 16 * t * C::VROW + 64 * db;
-                const bf16x8 sh = __builtin_shufflevector(lds_read_tr(p), lds_read_tr(p + 4 * C::VROW), 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 sl = __builtin_shufflevector(lds_read_tr(p + C::SS_BYTES), lds_read_tr(p + C::SS_BYTES + 4 * C::VROW),
+                const bf16x8 sh = __builtin_shufflevector(lds_read_tr(p), lds_read_tr(p + s_second), 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 sl = __builtin_shufflevector(lds_read_tr(p + C::SS_BYTES), lds_read_tr(p + C::SS_BYTES + s_second),
                                                           0, 1, 2, 3, 4, 5, 6, 7);
                 inter[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sh, qf[t], inter[db], 0, 0, 0);
                 inter[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sl, qf[t], inter[db], 0, 0, 0);

@@ -132,6 +132,19 @@ def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
     assert ex(d, ql=0x5000) == 1                          # out aliases q_lin
 
 
+def test_fused_feature_map_readout_rejects_bad_arguments(A):
+    lib = A.load_library()
+    d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    fm = lambda d, xq=0x6000, W=0x7000, c=0x8000, s=0x9000, S=0x4000, out=0x5000: lib.arl2_hybrid_attn_fwd_fm(
+        ctypes.byref(d), 0x1000, 0x2000, 0x3000, xq, W, c, s, S, None, out)
+    assert fm(d, S=None) == 1                             # no state, no linear branch
+    assert fm(d, xq=None) == 1
+    assert fm(d, s=None) == 1                             # cosines without sines
+    assert fm(d, out=0x6000) == 1                         # out aliases xq
+    assert fm(A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)) == 2
+    assert fm(A.make_desc(1, 2, 64, 32, 64, A.ARL2_BF16, stream=0)) == 1
+
+
 def test_gate_proj_rejects_bad_arguments(A):
     lib = A.load_library()
     d = A.make_desc(1, 12, 64, 64, 128, A.ARL2_BF16, stream=0)

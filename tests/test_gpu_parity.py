@@ -521,6 +521,33 @@ def test_readout_with_own_linear_query(lib, oracle, io):
     assert torch.equal(o1, o2)
 
 
+@pytest.mark.parametrize("D,L,rope", [(128, 328, True), (64, 200, True), (128, 257, False)])
+def test_readout_with_fused_feature_map(lib, oracle, D, L, rope):
+    """arl2_hybrid_attn_fwd_fm against the oracle chain (feature map in fp64, rounded to bf16 where the
+    kernel rounds its fragments, then the readout with that query), and against the two-launch path."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"fm{D}", D=D, L=L)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    xq = W.normal(22, w, (w.B, w.L, w.H, w.D), 0, 0, 104)
+    Wq, _, _ = W.feature_weights(w)
+    cs, sn = W.rope_tables(w) if rope else (None, None)
+    S = W.normal(23, w, (w.B, w.H, w.D, w.D), 0, 0, 105, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd_fm(dev(q), dev(k), dev(v), dev(xq), dev(Wq), dev(cs), dev(sn), dev(S), dev(g), out)
+    torch.cuda.synchronize()
+    ql_ref = to_np(_bf16_round(oracle.feature_map(to_np(xq), to_np(Wq), None if cs is None else to_np(cs), None if sn is None else to_np(sn))))
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(g), q_lin=ql_ref)
+    e = rel_err(to_np(out), ref)
+    assert e <= TOL_BF16_OUT, f"D={D} L={L}: {e:.3e}"
+    # the two-launch path computes the same thing: same MFMA order, same roundings
+    ql = torch.empty_like(q, device="cuda")
+    out2 = torch.empty_like(out)
+    lib.arl2_feature_map(dev(xq), dev(Wq), dev(cs), dev(sn), ql)
+    lib.arl2_hybrid_attn_fwd_ex(dev(q), dev(k), dev(v), ql, dev(S), dev(g), out2)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(out), to_np(out2).astype(np.float64)) <= 2.0 ** -7
+
+
 def _feature_chain(lib, oracle, w, rows=None):
     """Eq. (2)-(7) with the feature maps in place, from pre-RoPE projections: one readout pass and one
     commit on the GPU, and the same chain in the oracle (intermediates rounded to bf16 where the GPU
