@@ -106,7 +106,7 @@ static void fwd_row_f64(int H, int Lkv, int D,
  */
 int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                      const float *q, const float *k, const float *v, const float *q_lin,
-                     const double *S, const float *g, int g_per_element,
+                     const double *S, const float *g, int g_mode,
                      double sm_scale, double l2_eps,
                      const int32_t *rows, int nrows,
                      double *out);
@@ -125,12 +125,13 @@ int arl2o_fwd_f64(int B, int H, int Lq, int Lkv, int D,
  * The same pass with the inter branch's query given apart: q_lin [B][Lq][H][D] holds RoPE(phi_q(Q))
  * of Eq. (3), which the inter branch normalises and multiplies with S (Eq. (5)), while the intra
  * branch keeps q (Eq. (2)).  q_lin == NULL: the inter branch normalises q itself.
- * g_per_element != 0: g is [B][Lq][H][D], one gate per output feature (the element-wise gate of the
- * paper's gate-granularity ablation) instead of the headwise [B][Lq][H] of Eq. (6).
+ * g_mode selects the gate granularity of the paper's gate ablation: 0 = headwise g [B][Lq][H] (Eq. (6)),
+ * 1 = element-wise g [B][Lq][H][D] (one gate per output feature), 2 = scalar g [B][Lq] (one gate per
+ * token, shared by the heads).
  */
 int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                      const float *q, const float *k, const float *v, const float *q_lin,
-                     const double *S, const float *g, int g_per_element,
+                     const double *S, const float *g, int g_mode,
                      double sm_scale, double l2_eps,
                      const int32_t *rows, int nrows,
                      double *out)
@@ -157,8 +158,8 @@ int arl2o_fwd_ex_f64(int B, int H, int Lq, int Lkv, int D,
                 const float *v_bh = v + ((size_t)b * Lkv * H + h) * D;
                 const double *S_bh = S ? S + ((size_t)b * H + h) * D * D : NULL;
                 const size_t gi = ((size_t)b * Lq + i) * H + h;
-                const double g_i = (g && !g_per_element) ? (double)g[gi] : 1.0;
-                const float *g_vec = (g && g_per_element) ? g + gi * D : NULL;
+                const double g_i = (g && g_mode == 0) ? (double)g[gi] : (g && g_mode == 2) ? (double)g[(size_t)b * Lq + i] : 1.0;
+                const float *g_vec = (g && g_mode == 1) ? g + gi * D : NULL;
                 double *out_row = out + (((size_t)b * nrows + r) * H + h) * D;
                 const float *ql_row = q_lin ? q_lin + (((size_t)b * Lq + i) * H + h) * D : q_row;
                 fwd_row_f64(H, Lkv, D, q_row, ql_row, k_bh, v_bh, S_bh, g_i, g_vec, sm_scale, l2_eps,

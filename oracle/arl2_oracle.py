@@ -97,7 +97,8 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
 
     ``q_lin`` (fp64 path only), if given, is the row the inter branch normalises instead of q:
     RoPE(phi_q(Q)) of Eq. (3).  A 4-dimensional ``g`` [B, Lq, H, D] (fp64 path only) is one gate per
-    output feature, the element-wise granularity of the paper's gate ablation.
+    output feature and a 2-dimensional ``g`` [B, Lq] one gate per token shared by the heads: the
+    element-wise and the scalar granularity of the paper's gate ablation.
 
     ``rows`` restricts the computation to those query indices (each output row
     depends only on its own q row and on all of k, v, S); the result is then
@@ -109,9 +110,12 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
     st = np.float64 if precision == "f64" else np.float32
     S = None if S is None else _c(S, st)
     g_elem = g is not None and g.ndim == 4
+    g_tok = g is not None and g.ndim == 2
     if g_elem and g.shape != q.shape:
         raise ValueError("an element-wise gate must have the shape of q")
-    B, H, Lq, Lkv, D = _check_shapes(q, k, v, S, None if g_elem else g)
+    if g_tok and g.shape != q.shape[:2]:
+        raise ValueError("a scalar gate must be [B, Lq]")
+    B, H, Lq, Lkv, D = _check_shapes(q, k, v, S, None if (g_elem or g_tok) else g)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(D)  # Eq. (1)
     if rows is None:
@@ -122,15 +126,15 @@ def fwd(q, k, v, S=None, g=None, *, sm_scale: Optional[float] = None, l2_eps: fl
         if nrows and (rows_arr.min() < 0 or rows_arr.max() >= Lq):
             raise ValueError("row index out of range")
     out = np.empty((B, nrows, H, D), dtype=st)
-    if q_lin is not None or g_elem:
+    if q_lin is not None or g_elem or g_tok:
         if precision != "f64":
-            raise ValueError("q_lin and element-wise gates are supported by the fp64 oracle only")
+            raise ValueError("q_lin and element-wise or scalar gates are supported by the fp64 oracle only")
         if q_lin is not None:
             q_lin = _c(q_lin, np.float32)
             if q_lin.shape != q.shape:
                 raise ValueError("q_lin must have the shape of q")
         rc = lib.arl2o_fwd_ex_f64(B, H, Lq, Lkv, D, _ptr(q), _ptr(k), _ptr(v), _ptr(q_lin), _ptr(S), _ptr(g),
-                                  int(g_elem), float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
+                                  1 if g_elem else 2 if g_tok else 0, float(sm_scale), float(l2_eps), _ptr(rows_arr), nrows, _ptr(out))
         if rc != 0:
             raise MemoryError("oracle fwd failed")
         return out
@@ -222,7 +226,8 @@ def feature_map(x, W, cos=None, sin=None) -> np.ndarray:
 
 
 def gate_proj(x, Wg) -> np.ndarray:
-    """Headwise mix gate of Eq. (6): sigmoid(x W_g).  x [B, L, dm]; Wg [H, dm] (one row per head); fp64 [B, L, H]."""
+    """Mix gate of Eq. (6): sigmoid(x W_g).  x [B, L, dm]; Wg [n, dm], one row per gate output (n = H for
+    the headwise gate, 1 for the scalar gate of the gate ablation); fp64 [B, L, n]."""
     lib = _load()
     x, Wg = _c(x, np.float32), _c(Wg, np.float32)
     if x.ndim != 3 or Wg.ndim != 2 or Wg.shape[1] != x.shape[2]:

@@ -579,3 +579,12 @@ def test_gate_granularities(oracle):
     gt = rng.uniform(0.2, 0.8, (B, L, 1)).astype(np.float32)
     got = oracle.fwd(q, k, v, S, np.repeat(gt, H, axis=2))
     np.testing.assert_allclose(got, intra + gt[..., None].astype(np.float64) * inter, rtol=1e-12, atol=1e-13)
+    # ... and the [B, L] scalar gate is that array without the repetition
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, S, gt[..., 0]), got)
+    np.testing.assert_array_equal(oracle.fwd(q, k, v, S, gt[..., 0], rows=[5, 0]), got[:, [5, 0]])
+    with pytest.raises(ValueError):
+        oracle.fwd(q, k, v, S, np.ones((B, L + 1), np.float32))
+    # its projection has a single weight row (d_model parameters per layer)
+    from scipy.special import expit
+    x, w1 = rand(B, L, H * D), rand(1, H * D, scale=0.3)
+    np.testing.assert_allclose(oracle.gate_proj(x, w1)[..., 0], expit(x.astype(np.float64) @ w1[0].astype(np.float64)), rtol=1e-13)
