@@ -62,10 +62,11 @@ typedef enum {
 
 typedef enum { ARL2_F32 = 0, ARL2_BF16 = 1 } arl2_dtype;
 
-/* Granularity of the branch-mix gate g of the readout pass.  The paper's gate is headwise (Eq. (6));
- * its gate ablation also has one gate per token (pass the headwise array with equal entries per head)
- * and one gate per output feature (ARL2_GATE_PER_ELEMENT, g of shape [B][Lq][H][D], 16-byte aligned). */
-typedef enum { ARL2_GATE_PER_HEAD = 0, ARL2_GATE_PER_ELEMENT = 1 } arl2_gate_mode;
+/* Granularity of the branch-mix gate g of the readout pass.  The paper's gate is headwise (Eq. (6),
+ * g of shape [B][Lq][H]); its gate ablation (Tab. 4) also has one gate per output feature
+ * (ARL2_GATE_PER_ELEMENT, g of shape [B][Lq][H][D], 16-byte aligned) and a scalar gate, one per token
+ * shared by the heads (ARL2_GATE_PER_TOKEN, g of shape [B][Lq]). */
+typedef enum { ARL2_GATE_PER_HEAD = 0, ARL2_GATE_PER_ELEMENT = 1, ARL2_GATE_PER_TOKEN = 2 } arl2_gate_mode;
 
 typedef struct {
     int32_t B;            /* independent streams, >= 1                                      */
@@ -150,12 +151,15 @@ arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W
                              const float *rope_cos, const float *rope_sin, void *y);
 
 /*
- * Headwise branch-mix gate, paper Eq. (6): G = sigmoid(x W_g), the g argument of the readout pass.
+ * Branch-mix gate, paper Eq. (6): G = sigmoid(x W_g), the g argument of the readout pass.
  *   x         device bf16 [B][Lq][H*D], the layer's hidden state (desc->io_dtype must be ARL2_BF16).
- *   Wg        device bf16 [H][H*D]: row h is column h of the paper's (H*D) x H matrix W_g.
- *   g         device [B][Lq][H] in desc->g_dtype, fully overwritten; must not alias an input.
- * Up to 32 heads.  fp32 accumulation and sigmoid.  (A gate per token shared by all heads, or any other
- * gate already in [B][Lq][H] form, needs no kernel of its own: the readout takes it as it is.)
+ *   Wg        device bf16 [n][H*D], one row per gate output: n = H for desc->g_mode == ARL2_GATE_PER_HEAD
+ *             (row h is column h of the paper's (H*D) x H matrix W_g), n = 1 for ARL2_GATE_PER_TOKEN
+ *             (the scalar gate of the paper's gate ablation, Tab. 4).
+ *   g         device [B][Lq][n] in desc->g_dtype, fully overwritten; must not alias an input.
+ * Up to 32 heads.  fp32 accumulation and sigmoid.  ARL2_GATE_PER_ELEMENT returns ARL2_ERR_UNSUPPORTED:
+ * that projection is a dense (H*D) x (H*D) matrix product, a job for a BLAS library, whose output the
+ * readout pass takes as it is.
  */
 arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg, void *g);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libarl2_hip.so")
 
 ARL2_OK, ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED, ARL2_ERR_WORKSPACE, ARL2_ERR_DEVICE = range(5)
 ARL2_F32, ARL2_BF16 = 0, 1
-ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT = 0, 1
+ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT, ARL2_GATE_PER_TOKEN = 0, 1, 2
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
            "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_hybrid_attn_fwd_fm", "arl2_feature_map", "arl2_gate_proj",
@@ -135,6 +135,17 @@ def arl2_workspace_bytes(B: int, H: int, L: int, D: int, io_dtype) -> int:
     return int(load_library().arl2_workspace_bytes(ctypes.byref(d)))
 
 
+def _gate_layout(d: arl2_desc, g: Optional[torch.Tensor], B: int, Lq: int, H: int, D: int) -> tuple:
+    """Sets d.g_mode from the rank of g and returns the shape g must have."""
+    if g is not None and g.dim() == 4:                    # one gate per output feature
+        d.g_mode = ARL2_GATE_PER_ELEMENT
+        return (B, Lq, H, D)
+    if g is not None and g.dim() == 2:                    # one gate per token, shared by the heads
+        d.g_mode = ARL2_GATE_PER_TOKEN
+        return (B, Lq)
+    return (B, Lq, H)
+
+
 def arl2_hybrid_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                          S: Optional[torch.Tensor], g: Optional[torch.Tensor], out: torch.Tensor,
                          *, sm_scale: float = 0.0, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
@@ -146,9 +157,7 @@ def arl2_hybrid_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     io = _dtype_code(q)
     d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
                   stream=stream)
-    g_shape = (B, Lq, H)
-    if g is not None and g.dim() == 4:                    # one gate per output feature
-        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
+    g_shape = _gate_layout(d, g, B, Lq, H, D)
     st = load_library().arl2_hybrid_attn_fwd(
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
@@ -168,9 +177,7 @@ def arl2_hybrid_attn_fwd_ex(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q
     io = _dtype_code(q)
     d = make_desc(B, H, Lq, Lkv, D, io, _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
                   stream=stream)
-    g_shape = (B, Lq, H)
-    if g is not None and g.dim() == 4:                    # one gate per output feature
-        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
+    g_shape = _gate_layout(d, g, B, Lq, H, D)
     st = load_library().arl2_hybrid_attn_fwd_ex(
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
@@ -191,9 +198,7 @@ def arl2_hybrid_attn_fwd_fm(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, x
     Lkv = k.shape[1]
     d = make_desc(B, H, Lq, Lkv, D, _dtype_code(q), _dtype_code(g) if g is not None else ARL2_F32, sm_scale, l2_eps,
                   stream=stream)
-    g_shape = (B, Lq, H)
-    if g is not None and g.dim() == 4:
-        d.g_mode, g_shape = ARL2_GATE_PER_ELEMENT, (B, Lq, H, D)
+    g_shape = _gate_layout(d, g, B, Lq, H, D)
     st = load_library().arl2_hybrid_attn_fwd_fm(
         ctypes.byref(d),
         _dev(q, "q"), _dev(k, "k", (B, Lkv, H, D), q.dtype), _dev(v, "v", (B, Lkv, H, D), q.dtype),
@@ -219,18 +224,26 @@ def arl2_feature_map(x: torch.Tensor, W: torch.Tensor, rope_cos: Optional[torch.
     _check(st)
 
 
-def arl2_gate_proj(x: torch.Tensor, Wg: torch.Tensor, g: torch.Tensor, *, stream: Optional[int] = None) -> None:
-    """g = sigmoid(x Wg^T): the headwise mix gate of Eq. (6).  x [B, L, H*D] bf16, Wg [H, H*D] bf16,
-    g [B, L, H] fp32 or bf16 (written)."""
+def arl2_gate_proj(x: torch.Tensor, Wg: torch.Tensor, g: torch.Tensor, *, heads: Optional[int] = None,
+                   stream: Optional[int] = None) -> None:
+    """g = sigmoid(x Wg^T): the mix gate of Eq. (6).  x [B, L, H*D] bf16.  Headwise: Wg [H, H*D] bf16,
+    g [B, L, H] fp32 or bf16 (written).  Scalar gate (one per token): Wg [1, H*D], g [B, L], and ``heads``
+    names H."""
     if x.dim() != 3 or Wg.dim() != 2:
-        raise ValueError("x must be [B, L, H*D] and Wg [H, H*D]")
+        raise ValueError("x must be [B, L, H*D] and Wg [H, H*D] or [1, H*D]")
     B, L, dm = x.shape
-    H = Wg.shape[0]
-    if dm % H:
+    scalar = g.dim() == 2
+    if scalar and heads is None:
+        raise ValueError("a scalar gate needs the number of heads")
+    H = heads if heads is not None else Wg.shape[0]
+    if H < 1 or dm % H:
         raise ValueError("the hidden size must be a multiple of the number of heads")
     d = make_desc(B, H, L, L, dm // H, _dtype_code(x), _dtype_code(g), stream=stream)
-    st = load_library().arl2_gate_proj(ctypes.byref(d), _dev(x, "x"), _dev(Wg, "Wg", (H, dm), x.dtype),
-                                       _dev(g, "g", (B, L, H)))
+    if scalar:
+        d.g_mode = ARL2_GATE_PER_TOKEN
+    st = load_library().arl2_gate_proj(ctypes.byref(d), _dev(x, "x"),
+                                       _dev(Wg, "Wg", (1 if scalar else H, dm), x.dtype),
+                                       _dev(g, "g", (B, L) if scalar else (B, L, H)))
     _check(st)
 
 

@@ -28,7 +28,7 @@ arl2_status check_desc(const arl2_desc *d)
         return fail(ARL2_ERR_INVALID_ARG, "io_dtype is not an arl2_dtype");
     if (d->g_dtype != ARL2_F32 && d->g_dtype != ARL2_BF16)
         return fail(ARL2_ERR_INVALID_ARG, "g_dtype is not an arl2_dtype");
-    if (d->g_mode != ARL2_GATE_PER_HEAD && d->g_mode != ARL2_GATE_PER_ELEMENT)
+    if (d->g_mode != ARL2_GATE_PER_HEAD && d->g_mode != ARL2_GATE_PER_ELEMENT && d->g_mode != ARL2_GATE_PER_TOKEN)
         return fail(ARL2_ERR_INVALID_ARG, "g_mode is not an arl2_gate_mode");
     if (d->D != 64 && d->D != 128) return fail(ARL2_ERR_UNSUPPORTED, "D must be 64 or 128");
     if (!(d->sm_scale >= 0.f) || !(d->l2_eps >= 0.f))
@@ -89,6 +89,7 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
     a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     a.g_per_element = desc->g_mode == ARL2_GATE_PER_ELEMENT;
+    a.g_per_token = desc->g_mode == ARL2_GATE_PER_TOKEN;
     a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
     a.l2_eps = resolved_eps(desc);
     hipStream_t stream = reinterpret_cast<hipStream_t>(desc->stream);
@@ -134,6 +135,7 @@ arl2_status arl2_hybrid_attn_fwd_fm(const arl2_desc *desc, const void *q, const 
     a.B = desc->B; a.H = desc->H; a.Lq = desc->Lq; a.Lkv = desc->Lkv; a.D = desc->D;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     a.g_per_element = desc->g_mode == ARL2_GATE_PER_ELEMENT;
+    a.g_per_token = desc->g_mode == ARL2_GATE_PER_TOKEN;
     a.sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->D);
     a.l2_eps = resolved_eps(desc);
     const hipError_t e = arl2::launch_fwd_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
@@ -176,12 +178,15 @@ arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg,
     if (g == x || g == Wg) return fail(ARL2_ERR_INVALID_ARG, "g must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj takes bf16 x, Wg only");
     if (desc->H > 32) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj supports up to 32 heads");
+    if (desc->g_mode == ARL2_GATE_PER_ELEMENT)
+        return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj has no element-wise mode (a dense matrix product)");
     if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
 
     arl2::GateArgs a;
     a.x = x; a.Wg = Wg; a.g = g;
     a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.dm = desc->H * desc->D;
+    a.n_out = desc->g_mode == ARL2_GATE_PER_TOKEN ? 1 : desc->H;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     const hipError_t e = arl2::launch_gate_proj_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
     if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "gate projection launch failed: %s", hipGetErrorString(e));

@@ -36,6 +36,7 @@ struct FwdArgs {
     int B, H, Lq, Lkv, D;
     int g_is_bf16;
     int g_per_element;     // g is [B][Lq][H][D] instead of [B][Lq][H]
+    int g_per_token;       // g is [B][Lq]: one gate per token, shared by the heads
     float sm_scale;        // already resolved (never 0)
     float l2_eps;          // already resolved
 };
@@ -61,9 +62,10 @@ struct FmapArgs {
 
 struct GateArgs {
     const void *x;         // [B][L][dm] bf16, dm = H * D
-    const void *Wg;        // [H][dm] bf16
-    void *g;               // [B][L][H], fp32 or bf16
+    const void *Wg;        // [n_out][dm] bf16
+    void *g;               // [B][L][n_out], fp32 or bf16
     int B, H, L, dm;
+    int n_out;             // gate outputs per token: H (headwise) or 1 (scalar)
     int g_is_bf16;
 };
 

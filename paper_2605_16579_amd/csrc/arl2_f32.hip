@@ -94,10 +94,10 @@ __global__ __launch_bounds__(NT) void fwd_f32_kernel(FwdArgs a)
                 for (int e = 0; e < EPL; ++e) oi[e] = fmaf(qd, Sg[(size_t)d * D + e], oi[e]);
             }
         }
-        const size_t gi = ((size_t)b * Lq + rowc) * H + h;
+        const size_t gi = a.g_per_token ? (size_t)b * Lq + rowc : ((size_t)b * Lq + rowc) * H + h;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-            float g = 1.0f;                  // headwise gate, or one gate per output feature
+            float g = 1.0f;                  // headwise or per-token gate, or one gate per output feature
             if (a.g != nullptr) {
                 const size_t ge = a.g_per_element ? gi * D + sub * EPL + i : gi;
                 g = a.g_is_bf16 ? (float)((const bf16_t *)a.g)[ge] : ((const float *)a.g)[ge];

@@ -493,7 +493,8 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
             }
         // gate * L2 norm scale for this lane's query row
         float gq = 1.0f / sqrtf(qss + a.l2_eps);
-        const size_t gi = ((size_t)b * Lq + (qrow < Lq ? qrow : 0)) * H + h;
+        const size_t gtok = (size_t)b * Lq + (qrow < Lq ? qrow : 0);
+        const size_t gi = a.g_per_token ? gtok : gtok * H + h;
         if (a.g != nullptr && !a.g_per_element && qrow < Lq)
             gq *= a.g_is_bf16 ? (float)((const bf16_t *)a.g)[gi] : ((const float *)a.g)[gi];
         if (a.g != nullptr && a.g_per_element) {

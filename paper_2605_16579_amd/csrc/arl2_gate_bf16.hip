@@ -1,6 +1,7 @@
-// Headwise branch-mix gate on bf16 MFMA (gfx950):
-//   G[b][l][h] = sigmoid( sum_j x[b][l][j] Wg[h][j] )                        paper Eq. (6)
-// x is the layer's hidden state [B][L][dm], dm = H D; Wg holds one row of dm weights per head.
+// Branch-mix gate on bf16 MFMA (gfx950):
+//   G[b][l][n] = sigmoid( sum_j x[b][l][j] Wg[n][j] )                        paper Eq. (6)
+// x is the layer's hidden state [B][L][dm], dm = H D; Wg holds one row of dm weights per gate output:
+// one per head (the paper's headwise gate) or a single one (the scalar gate of its gate ablation, Tab. 4).
 // HBM-bound: x is read once (2 H flop per byte).  Computed transposed, G^T[h][l] = Wg x^T, so that both
 // operands are read as rows; the H <= 32 heads occupy the rows of one 32 x 32 MFMA tile (rows >= H are
 // zero).  One workgroup owns 32 tokens; its four wavefronts split dm and add their partial sums in LDS.
@@ -21,7 +22,7 @@ __global__ __launch_bounds__(NT) void gate_proj_kernel(GateArgs a)
     __shared__ float part[4][16][64];                    // [wavefront][register][lane]
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c = lane & 31;
-    const int dm = a.dm, H = a.H;
+    const int dm = a.dm, H = a.n_out;                    // rows of Wg = gate outputs per token
     const long long tok0 = (long long)blockIdx.x * 32;   // first token (over streams and chunk positions)
     const long long ntok = (long long)a.B * a.L;
 
@@ -67,7 +68,7 @@ hipError_t launch_gate_proj_bf16(const GateArgs &a, hipStream_t stream)
     const long long ntok = (long long)a.B * a.L;
     const long long nwg = (ntok + 31) / 32;
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.H < 1 || a.H > 32 || a.dm % 16 != 0) return hipErrorInvalidValue;
+    if (a.n_out < 1 || a.n_out > 32 || a.dm % 16 != 0) return hipErrorInvalidValue;
     // x is addressed with 32-bit byte offsets
     if (ntok * a.dm * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(gate_proj_kernel, dim3((unsigned)nwg), dim3(NT), 0, stream, a);

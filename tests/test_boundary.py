@@ -169,6 +169,10 @@ def test_sizes_beyond_the_kernels_addressing_are_refused(A):
     many = A.make_desc(64, 12, 32768, 32768, 128, A.ARL2_BF16, stream=0)     # each stream small, x as a whole 6.4 GB
     assert lib.arl2_feature_map(ctypes.byref(many), 0x1000, 0x2000, None, None, 0x5000) == 2
     assert lib.arl2_gate_proj(ctypes.byref(many), 0x1000, 0x2000, 0x3000) == 2
+    de = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    de.g_mode = A.ARL2_GATE_PER_ELEMENT
+    assert lib.arl2_gate_proj(ctypes.byref(de), 0x1000, 0x2000, 0x3000) == 2   # a dense product: not this library's job
+    assert b"element-wise" in lib.arl2_last_error()
     empty = A.make_desc(1, 2, 0, 0, 64, A.ARL2_BF16, stream=0)               # no tokens
     assert lib.arl2_hybrid_attn_fwd(ctypes.byref(empty), 0x1000, 0x2000, 0x3000, None, None, 0x5000) == 1
 

@@ -661,6 +661,40 @@ def test_elementwise_gate(lib, oracle, io, gdt):
     assert torch.equal(o1, o2)
 
 
+@pytest.mark.parametrize("io,gdt", [("bf16", "f32"), ("bf16", "bf16"), ("f32", "f32")])
+def test_scalar_gate(lib, oracle, io, gdt):
+    """One gate per token shared by the heads ([B, L]), the coarsest granularity of the paper's gate
+    ablation (Tab. 4), projected on the GPU from a single weight row and used by the readout."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="gate_tok_" + io, io_dtype=io, L=200 if io == "f32" else 328)
+    q, k, v, _ = W.pass_inputs(w, 0, 0)
+    wb = dataclasses.replace(w, io_dtype="bf16")
+    x, Wg = W.gate_inputs(wb, 0, 0)
+    w1 = (Wg[:1] * 8.0).contiguous()                        # one weight row: d_model parameters
+    gt = torch.full((w.B, w.L), -1.0, dtype=torch.float32 if gdt == "f32" else torch.bfloat16, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(w1), gt, heads=w.H)
+    torch.cuda.synchronize()
+    g_ref = oracle.gate_proj(to_np(x), to_np(w1))[..., 0]
+    assert g_ref.min() < 0.35 and g_ref.max() > 0.65
+    err = np.abs(to_np(gt) - g_ref).max()
+    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9), f"{err:.3e}"
+    S = W.normal(20, w, (w.B, w.H, w.D, w.D), 0, 0, 104, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), gt, out)
+    torch.cuda.synchronize()
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(gt))   # the gate values the GPU read
+    e = rel_err(to_np(out), ref)
+    assert e <= (TOL_BF16_OUT if io == "bf16" else 1e-4), f"{io}/{gdt}: {e:.3e}"
+    ref2 = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), g_ref.astype(np.float32))   # the oracle's own gates
+    assert rel_err(to_np(out), ref2) <= (TOL_BF16_OUT if io == "bf16" else 1e-4)
+    # repeated for every head it is the headwise gate, bit for bit
+    gh = gt[..., None].expand(-1, -1, w.H).contiguous()
+    o2 = torch.empty_like(out)
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), gh, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, o2)
+
+
 def test_degenerate_rows(lib, oracle):
     """All-zero query and key rows (L2Norm gives 0, not NaN), identical keys (uniform softmax), and a
     state commit whose keys are all zero (only the gate acts)."""
