@@ -21,6 +21,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 // MI355X has 8 accelerator dies (XCDs), each with its own L2; the hardware deals
 // consecutive workgroup ids to the XCDs round-robin.
 constexpr int kNumXcd = 8;
+constexpr int kNumCu = 256;
 constexpr int kWave = 64;
 
 struct FwdArgs {

@@ -23,7 +23,8 @@
 // Kernel 2 walks the blocks in order: one workgroup per (stream, head, 32 state columns), the state
 // slice in accumulator registers, S <- gam S + Psi + (-E) S with -E hi/lo against S hi/lo (three MFMA
 // terms, the lo x lo term is below fp32 rounding), the slice exchanged between wavefronts through LDS
-// in the same k-slot order.
+// in the same k-slot order.  With few heads the blocks of a head are cut into runs that are walked at
+// the same time, each later run producing its composite map, and a second launch applies those in order.
 // All products of gates are formed by multiplication only, so gates of exactly zero are handled.
 #include "arl2_device.h"
 
@@ -419,32 +420,72 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
 }
 
 // ---- kernel 2: S <- gam S + Psi + (-E) S over the blocks in order ---------------------------------------
-template <int D>
-__global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
+// The same walk serves three purposes.
+//   GROUPED == false: one workgroup per (stream, head, 32 state columns) applies the `count` maps stored
+//     at `maps` (per head `head_stride` records apart) to the state in a.S.
+//   GROUPED == true: the blocks of a head are cut into `groups` runs of consecutive blocks that are walked
+//     at the same time.  Run 0 starts from the state in a.S and leaves X_0 there.  Every later run g
+//     computes its own composite map: the walk is applied to the columns of the identity (giving
+//     M_g = prod (gam_n I - E_n)) and to zero (giving c_g), 32 columns per workgroup, and the result is
+//     stored as one more record of the block format, -E := M_g - gam_g I with gam_g = prod gam_n (the
+//     multiple of the identity stays an exact fp32 scalar), Psi := c_g.  A second, ungrouped launch then
+//     applies the groups - 1 composite maps to X_0 in order.  For few heads this shortens the sequential
+//     chain from nblk steps to nblk / groups + groups - 1.
+template <int D, bool GROUPED>
+__global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsigned char *maps, int head_stride, int count,
+                                                          int nblk, int groups, unsigned char *gmaps)
 {
     constexpr int KS = D / 16;                           // k-steps of the D-long contraction
+    constexpr int NSL = D / 32;                          // 32-column slices of the state
     constexpr int SROW = 2 * D + 16;                     // LDS bytes per state column (conflict-free b128 reads)
     constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row slot]
     constexpr int PFD = GDN_PFD, NBUF = PFD + 1;
     constexpr int EARLY = GDN_EARLY;                             // k-steps whose loads are issued before the MFMAs start
+    constexpr int TROW = 64 + 16;                        // LDS bytes per row of the [D][32] bf16 tile that transposes M_g
+    static_assert(2 * D * TROW <= 4 * SBUF, "the transposing tiles must fit into the exchange buffers");
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * SBUF];   // [buffer][hi, lo]
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
-    // The column slices of one head read the same -E: all of them run on one XCD (consecutive workgroup
-    // ids go round the 8 XCDs), so that its L2 serves the re-reads.  The grid is padded to whole heads per XCD.
-    const int xcd = blockIdx.x % kNumXcd, loc = blockIdx.x / kNumXcd;
-    const int slice = loc % (D / 32);
-    const int bh = (loc / (D / 32)) * kNumXcd + xcd;
-    if (bh >= a.B * a.H) return;
+    // Workgroups that read the same -E run on one XCD (consecutive workgroup ids go round the 8 XCDs), so
+    // that its L2 serves the re-reads: the slices of a head, or of a (head, run) pair.  The grid is padded
+    // to whole owners per XCD.  Grouped: the runs after the first (2 NSL workgroups each, M and c slices)
+    // come first in the grid, then the first runs (NSL workgroups each, c slices only), each kind dealt
+    // round the XCDs on its own, so that every XCD gets the same number of busy workgroups.
+    const int heads = a.B * a.H;
+    const int n_late = GROUPED ? (heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL : 0;
+    const bool late = (int)blockIdx.x < n_late;           // a run after the first
+    const int id = late ? blockIdx.x : blockIdx.x - n_late;   // n_late is a multiple of 8: the XCD phase is kept
+    const int xcd = id % kNumXcd, loc = id / kNumXcd;
+    const int units = late ? 2 * NSL : NSL;
+    const int unit = loc % units;
+    const int owner = (loc / units) * kNumXcd + xcd;     // head, or (head, later run) pair
+    const int slice = unit % NSL;
+    const bool is_m = unit >= NSL;
+    int bh = owner, grp = 0, first = 0, n = count;
+    if constexpr (GROUPED) {
+        if (late) {
+            bh = owner / (groups - 1);
+            grp = 1 + owner % (groups - 1);
+        }
+        first = (int)((long long)grp * nblk / groups);
+        n = (int)((long long)(grp + 1) * nblk / groups) - first;
+    }
+    if (bh >= heads || n <= 0) return;
     float *Sg = a.S + (size_t)bh * D * D + 32 * slice + c32;
     const int row0 = 32 * wave + 4 * hh;                 // accumulator register r holds row row0 + 8 (r / 4) + r % 4
 
     f32x16 s_acc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s_acc[r] = Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D];
+    for (int r = 0; r < 16; ++r) {
+        const int row = row0 + 8 * (r >> 2) + (r & 3);
+        if (!GROUPED || grp == 0) s_acc[r] = Sg[(size_t)row * D];
+        else s_acc[r] = (is_m && row == 32 * slice + c32) ? 1.0f : 0.0f;
+    }
+    const float psi_on = is_m ? 0.0f : 1.0f;             // the identity's columns take no Psi
+    float gprod = 1.0f;                                  // gam of the blocks walked so far
 
-    const unsigned char *ws = (const unsigned char *)a.workspace + (size_t)bh * nblk * gdn_block_bytes(D);
+    const unsigned char *ws = maps + ((size_t)bh * head_stride + first) * gdn_block_bytes(D);
     // operands of the next PFD blocks are kept in flight (registers), a ring of NBUF = PFD + 1 buffers
     bf16x8 ehi[NBUF][KS], elo[NBUF][KS];
     f32x4 psi[NBUF][4];
@@ -460,7 +501,7 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
             ehi[buf][part] = Ehi[part * 64];
             elo[buf][part] = Ehi[D * D / 8 + part * 64];
         } else {                                         // its block of Psi, accumulator order
-            const f32x4 *Psi = (const f32x4 *)(p + (size_t)D * D * 4) + (wave * (D / 32) + slice) * 4 * 64 + lane;
+            const f32x4 *Psi = (const f32x4 *)(p + (size_t)D * D * 4) + (wave * NSL + slice) * 4 * 64 + lane;
 #pragma unroll
             for (int q = 0; q < 4; ++q) psi[buf][q] = Psi[q * 64];
             gam[buf] = *(const float *)(p + (size_t)D * D * 8);
@@ -478,7 +519,7 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
     auto step = [&](int blk, auto buf_) {
         constexpr int buf = decltype(buf_)::value;
         // past the last block this re-reads the last one (unused), which keeps the loop free of branches
-        const int nxt = blk + PFD < nblk ? blk + PFD : nblk - 1;
+        const int nxt = blk + PFD < n ? blk + PFD : n - 1;
         const std::integral_constant<int, (buf + PFD) % NBUF> nbuf{};
         fetch_part(nxt, nbuf, std::integral_constant<int, KS>{});
         static_for<0, EARLY>([&](auto part_) { fetch_part(nxt, nbuf, part_); });
@@ -507,29 +548,114 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, int nblk)
             if constexpr (t + EARLY < KS) fetch_part(nxt, nbuf, std::integral_constant<int, t + EARLY>{});
             __builtin_amdgcn_sched_barrier(0);
         });
+        const float psc = GROUPED ? psi_on : 1.0f;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            s_acc[r] = (fmaf(gam[buf], s_acc[r], psi[buf][r >> 2][r & 3]) + acc0[r]) + (acc1[r] + acc2[r]);
+            s_acc[r] = (fmaf(gam[buf], s_acc[r], psc * psi[buf][r >> 2][r & 3]) + acc0[r]) + (acc1[r] + acc2[r]);
+        if constexpr (GROUPED) gprod *= gam[buf];
     };
 
-    static_for<0, PFD>([&](auto i_) { fetch(decltype(i_)::value < nblk ? decltype(i_)::value : nblk - 1, i_); });
+    static_for<0, PFD>([&](auto i_) { fetch(decltype(i_)::value < n ? decltype(i_)::value : n - 1, i_); });
     int blk = 0;
 #pragma unroll 1
-    for (; blk + NBUF <= nblk; blk += NBUF)
+    for (; blk + NBUF <= n; blk += NBUF)
         static_for<0, NBUF>([&](auto i_) { step(blk + decltype(i_)::value, i_); });
     static_for<0, NBUF - 1>([&](auto i_) {
-        if (blk + decltype(i_)::value < nblk) step(blk + decltype(i_)::value, i_);
+        if (blk + decltype(i_)::value < n) step(blk + decltype(i_)::value, i_);
     });
 
+    if (!GROUPED || grp == 0) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D] = s_acc[r];
+        for (int r = 0; r < 16; ++r) Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D] = s_acc[r];
+        return;
+    }
+    if constexpr (GROUPED) {
+        // the composite map of run grp >= 1 as one record of the block format
+        unsigned char *rec = gmaps + ((size_t)bh * (groups - 1) + grp - 1) * gdn_block_bytes(D);
+        if (!is_m) {                                     // c_g, accumulator order: what the walk reads as Psi
+            f32x4 *Psi = (f32x4 *)(rec + (size_t)D * D * 4) + (wave * NSL + slice) * 4 * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) Psi[q * 64] = f32x4{s_acc[4 * q], s_acc[4 * q + 1], s_acc[4 * q + 2], s_acc[4 * q + 3]};
+            if (slice == 0 && tid == 0) *(float *)(rec + (size_t)D * D * 8) = gprod;
+            return;
+        }
+        // M_g - gam_g I, columns 32 slice .. + 31: through LDS into A-fragment order (lane = row, eight
+        // columns of k-steps 2 slice, 2 slice + 1 in k-slot order), hi and lo parts
+        __syncthreads();                                 // the exchange buffers are no longer read
+        unsigned char *Thi = smem, *Tlo = smem + D * TROW;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + 8 * (r >> 2) + (r & 3);
+            const float x = s_acc[r] - (row == 32 * slice + c32 ? gprod : 0.0f);
+            const bf16_t h = to_bf16(x);
+            *(bf16_t *)(Thi + row * TROW + 2 * c32) = h;
+            *(bf16_t *)(Tlo + row * TROW + 2 * c32) = to_bf16(x - (float)h);
+        }
+        __syncthreads();
+        bf16x8 *Ehi = (bf16x8 *)rec, *Elo = Ehi + D * D / 8;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {                    // 4 D fragment pieces, 2 D threads
+            const int p = tid + 2 * D * i;
+            const int ln = p & 63, tl = (p >> 6) & 1, rb = p >> 7;
+            const int off = (32 * rb + (ln & 31)) * TROW + 2 * (16 * tl + 4 * (ln >> 5));
+            const bf16x4 h0 = *(const bf16x4 *)(Thi + off), h1 = *(const bf16x4 *)(Thi + off + 16);
+            const bf16x4 l0 = *(const bf16x4 *)(Tlo + off), l1 = *(const bf16x4 *)(Tlo + off + 16);
+            const int idx = (rb * KS + 2 * slice + tl) * 64 + ln;
+            Ehi[idx] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+            Elo[idx] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
 }
 
 }  // namespace
 
+// Runs of blocks that are walked at the same time: as many as keep the walk within about one workgroup
+// per CU (the runs after the first cost twice the work), each at least four blocks long.
+static int gdn_groups(int B, int H, int nblk)
+{
+#ifdef GDN_GROUPS
+    int g = GDN_GROUPS;
+#else
+    const long long heads = (long long)B * H;
+    int g = (int)((kNumCu / (heads * 4) + 1) / 2);       // (2 g - 1) * 4 slices * heads <= CUs
+#endif
+    if (g > nblk / 4) g = nblk / 4;
+    if (g > 8) g = 8;
+    return g < 1 ? 1 : g;
+}
+
 size_t gdn_workspace_bytes(int B, int H, int L, int D)
 {
-    return (size_t)B * H * ((L + CT - 1) / CT) * gdn_block_bytes(D);
+    const int nblk = (L + CT - 1) / CT;
+    return (size_t)B * H * (nblk + gdn_groups(B, H, nblk) - 1) * gdn_block_bytes(D);
+}
+
+template <int D>
+static hipError_t launch_gdn(const GdnArgs &a, int nblk, unsigned nwg, hipStream_t stream)
+{
+    constexpr int NSL = D / 32;
+    const int heads = a.B * a.H;
+    const int groups = gdn_groups(a.B, a.H, nblk);
+    const unsigned char *maps = (const unsigned char *)a.workspace;
+    unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * gdn_block_bytes(D);
+    hipLaunchKernelGGL(gdn_block_kernel<D>, dim3(nwg), dim3(NTA), 0, stream, a, nblk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // whole owners per XCD: ceil(owners / 8) on each of the 8 XCDs
+    const unsigned nscan = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd * NSL);
+    if (groups == 1) {
+        hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, maps, nblk, nblk, nblk, 1,
+                           (unsigned char *)nullptr);
+        return hipGetLastError();
+    }
+    // the runs after the first (M and c slices), then the first runs (c slices), each padded to whole owners per XCD
+    const unsigned ngrp = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL) + nscan;
+    hipLaunchKernelGGL((gdn_scan_kernel<D, true>), dim3(ngrp), dim3(2 * D), 0, stream, a, maps, nblk, 0, nblk, groups, gmaps);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, (const unsigned char *)gmaps,
+                       groups - 1, groups - 1, nblk, 1, (unsigned char *)nullptr);
+    return hipGetLastError();
 }
 
 hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream)
@@ -539,22 +665,9 @@ hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream)
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
     // the block kernel addresses one stream's K (or V) with 32-bit byte offsets
     if ((long long)(a.L + 4 * CT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
-    // whole heads per XCD: ceil(B H / 8) heads on each of the 8 XCDs, D / 32 workgroups per head
-    const unsigned nscan = (unsigned)(((a.B * a.H + kNumXcd - 1) / kNumXcd) * kNumXcd * (a.D / 32));
-    if (a.D == 128) {
-        hipLaunchKernelGGL(gdn_block_kernel<128>, dim3((unsigned)nwg), dim3(NTA), 0, stream, a, nblk);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gdn_scan_kernel<128>, dim3(nscan), dim3(256), 0, stream, a, nblk);
-    } else if (a.D == 64) {
-        hipLaunchKernelGGL(gdn_block_kernel<64>, dim3((unsigned)nwg), dim3(NTA), 0, stream, a, nblk);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gdn_scan_kernel<64>, dim3(nscan), dim3(128), 0, stream, a, nblk);
-    } else {
-        return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    if (a.D == 128) return launch_gdn<128>(a, nblk, (unsigned)nwg, stream);
+    if (a.D == 64) return launch_gdn<64>(a, nblk, (unsigned)nwg, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace arl2

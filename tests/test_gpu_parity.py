@@ -368,8 +368,8 @@ def test_gdn_commit_small(lib, oracle, D, L):
 
 @pytest.mark.parametrize("D,L", [(128, 1700), (128, 3141), (64, 1700)])
 def test_gdn_commit_long_chunks(lib, oracle, D, L):
-    """Chunks long enough that the per-block maps are composed pairwise (one and two levels, with an
-    odd block left over at a level) before the in-order scan."""
+    """Chunks long enough that the blocks of a head are walked as several runs at the same time (six and
+    eight runs here, of lengths that differ by one), whose composite maps are then applied in order."""
     import dataclasses
     w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gdn_long{D}", B=1, H=2, D=D, L=L)
     S0 = W.normal(5, w, (w.B, w.H, w.D, w.D), 0, 0, 92, io_dtype="f32")
