@@ -89,48 +89,6 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
     out = torch.empty_like(q)
     S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
     ws = A.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype, device=dev)
-    rule = args.commit_rule
-    rule_cpu = None
-    if rule == "delta":       # learning rate in the range where the frame-level rule is a contraction (below 2 D / L)
-        rule_cpu = (W.uniform(0, w, (w.B, w.H), 0.2 * w.D / w.L, 1.0 * w.D / w.L, 0, 0, 77),)
-    elif rule == "gdn":
-        rule_cpu = W.token_gates(w, 0)
-        ws_gdn = torch.empty(A.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device=dev)
-    rule_dev = None if rule_cpu is None else tuple(t.to(dev) for t in rule_cpu)
-
-    gp = None
-    if args.gate_proj:
-        if w.io_dtype != "bf16":
-            print("bench.py: --gate-proj needs a bf16 workload", file=sys.stderr)
-            return 2
-        gp = [tuple(t.to(dev) for t in W.gate_inputs(w, 0, p)) for p in range(w.passes)]
-    n_read = w.passes + (1 if args.clean_readout else 0)
-    fm = None
-    if args.feature_maps:
-        if w.io_dtype != "bf16":
-            print("bench.py: --feature-maps needs a bf16 workload", file=sys.stderr)
-            return 2
-        Wq, Wk, Wv = (t.to(dev) for t in W.feature_weights(w))
-        cs, sn = (t.to(dev) for t in W.rope_tables(w))
-        fm = {"Wq": Wq, "Wk": Wk, "Wv": Wv, "cs": cs, "sn": sn, "ql": torch.empty_like(kc),
-              "kl": torch.empty_like(kc), "vl": torch.empty_like(kc)}
-
-    def commit():
-        if fm is not None:
-            A.arl2_feature_map(kc, fm["Wk"], fm["cs"], fm["sn"], fm["kl"])
-            A.arl2_feature_map(vc, fm["Wv"], None, None, fm["vl"])
-            kk, vv = fm["kl"], fm["vl"]
-        else:
-            kk, vv = kc, vc
-        _commit(kk, vv)
-
-    def _commit(kc, vc):
-        if rule == "plain":
-            A.arl2_state_commit(kc, vc, gate, S, ws)
-        elif rule == "delta":
-            A.arl2_state_commit_delta(kc, vc, gate, rule_dev[0], S, ws)
-        else:
-            A.arl2_state_commit_gdn(kc, vc, rule_dev[0], rule_dev[1], S, ws_gdn)
     A.arl2_state_commit(kc, vc, gate, S, ws)
     kv_k = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 101).to(dev)
     kv_v = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 102).to(dev)

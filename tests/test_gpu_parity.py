@@ -768,3 +768,15 @@ def test_chunk_step_replays_from_a_captured_graph(lib):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, out_ref) and torch.equal(S, S_ref)
+
+
+def test_bench_stack_report_runs(lib):
+    """The layer-stack report of bench.py (a harness around the same calls) on a shortened rollout."""
+    import importlib.util, os
+    spec = importlib.util.spec_from_file_location("arl2_bench", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    r = bench.stack_report(lib, W, torch, torch.device("cuda:0"), chunks=2, reps=1)
+    assert r["speedup"] > 1.0 and 0.0 < r["memory_ratio"] < 1.0
+    t = r["per_call_ms"]["softmax_kv_pass_by_cached_chunks"]
+    assert len(t) == 2 and t[1] > t[0] > 0.0
