@@ -34,7 +34,10 @@
 // Epilogue (fused linear readout): O_inter^T[e][q] = S^T[e][d] . Q^T[d][q] with the fp32
 // state split into bf16 hi + lo parts, staged row-major through the (now free) LDS and read
 // transposed like V, the raw bf16 q fragments as B operand, and the L2 norm of q applied as an
-// fp32 per-column scale.
+// fp32 per-column scale.  The linear branch may read a query of its own (Eq. (3): RoPE(phi_q(Q))):
+// either given as an array, or computed here from the pre-map rows and the head's D x D matrix, in
+// which case the rotated, rounded accumulators of that small GEMM are used as the B fragments
+// directly.  The gate is one value per (token, head) (Eq. (6)), per token, or per output feature.
 #include "arl2_device.h"
 
 #include <type_traits>
@@ -318,20 +321,33 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     const std::integral_constant<int, kS> S_{};
     const std::integral_constant<int, kPV> PV_{};
     const std::integral_constant<int, kNone> NONE_{};
-    prefetch_chain(S_, st_cur);
+    if (q0 < Lq) {
+        prefetch_chain(S_, st_cur);
 #pragma unroll 1
-    for (int it = 0; it < ntiles - 1; ++it) {
+        for (int it = 0; it < ntiles - 1; ++it) {
+            load_tile();
+            run_chain(S_, st_cur, PV_, st_cur);
+            softmax(0, unmasked);
+            run_chain(PV_, st_cur, S_, st_next);
+            close_interval();
+        }
         load_tile();
         run_chain(S_, st_cur, PV_, st_cur);
-        softmax(0, unmasked);
-        run_chain(PV_, st_cur, S_, st_next);
-        close_interval();
+        softmax((ntiles - 1) * BN, masked);
+        run_chain(PV_, st_cur, NONE_, 0);
+        __syncthreads();
+    } else {
+        // A wavefront whose 32 rows all lie past the last query (the ragged last workgroup of a head) only
+        // helps to move the tiles: the same loads, stores and barriers, no arithmetic.  Its rows are never
+        // stored.
+#pragma unroll 1
+        for (int it = 0; it < ntiles - 1; ++it) {
+            load_tile();
+            close_interval();
+        }
+        __syncthreads();
+        l_run = 1.0f;
     }
-    load_tile();
-    run_chain(S_, st_cur, PV_, st_cur);
-    softmax((ntiles - 1) * BN, masked);
-    run_chain(PV_, st_cur, NONE_, 0);
-    __syncthreads();
 
     // ---- epilogue ------------------------------------------------------------------------
     {
