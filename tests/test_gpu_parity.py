@@ -780,3 +780,38 @@ def test_bench_stack_report_runs(lib):
     assert r["speedup"] > 1.0 and 0.0 < r["memory_ratio"] < 1.0
     t = r["per_call_ms"]["softmax_kv_pass_by_cached_chunks"]
     assert len(t) == 2 and t[1] > t[0] > 0.0
+
+
+def _sweep_shapes():
+    """Seeded draw of problem shapes around the kernels' tile edges (32-row blocks, 64-key tiles, 256-row
+    workgroups), odd head counts and both head dimensions."""
+    r = np.random.default_rng(20240607)
+    Ls = [1, 2, 31, 32, 33, 63, 64, 65, 127, 129, 255, 256, 257, 300, 511, 513, 640]
+    shapes = []
+    for i in range(18):
+        shapes.append((int(r.integers(1, 4)), int(r.choice([1, 2, 3, 5, 9, 13])), int(r.choice(Ls)), int(r.choice([64, 128]))))
+    return shapes
+
+
+@pytest.mark.parametrize("B,H,L,D", _sweep_shapes())
+def test_shape_sweep(lib, oracle, B, H, L, D):
+    """One readout pass, one plain commit and one token-sequential commit per drawn shape, element by element."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"sweep_{B}_{H}_{L}_{D}", B=B, H=H, L=L, D=D)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    S0 = W.normal(23, w, (B, H, D, D), 0, 0, 105, io_dtype="f32") * 0.2
+    S64 = to_np(S0).astype(np.float64)
+    out = gpu_fwd(lib, q, k, v, S0, g)
+    e = rel_err(to_np(out), oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g)))
+    assert e <= TOL_BF16_OUT, f"readout {B}x{H}x{L}x{D}: {e:.3e}"
+    kc, vc, gate = W.clean_inputs(w, 0)
+    S_dev = dev(S0).clone()
+    gpu_commit(lib, kc, vc, gate, S_dev)
+    e = rel_err_per_head(to_np(S_dev), oracle.commit(to_np(kc), to_np(vc), to_np(gate), S64))
+    assert e <= TOL_STATE, f"commit {B}x{H}x{L}x{D}: {e:.3e}"
+    alpha, beta = W.token_gates(w, 0)
+    S_dev = dev(S0).clone()
+    lib.arl2_state_commit_gdn(dev(kc), dev(vc), dev(alpha), dev(beta), S_dev, _gdn_ws(lib, w))
+    torch.cuda.synchronize()
+    e = rel_err_per_head(to_np(S_dev), oracle.commit_gdn(to_np(kc), to_np(vc), to_np(alpha), to_np(beta), S64))
+    assert e <= TOL_STATE, f"gdn commit {B}x{H}x{L}x{D}: {e:.3e}"
