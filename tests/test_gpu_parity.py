@@ -815,3 +815,40 @@ def test_shape_sweep(lib, oracle, B, H, L, D):
     torch.cuda.synchronize()
     e = rel_err_per_head(to_np(S_dev), oracle.commit_gdn(to_np(kc), to_np(vc), to_np(alpha), to_np(beta), S64))
     assert e <= TOL_STATE, f"gdn commit {B}x{H}x{L}x{D}: {e:.3e}"
+
+
+@pytest.mark.parametrize("B,H,L,D", _sweep_shapes()[::2])
+def test_shape_sweep_maps_and_gates(lib, oracle, B, H, L, D):
+    """The feature map, the readout with the fused query map, and the headwise and scalar gate projections
+    on every other drawn shape."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"sweepfm_{B}_{H}_{L}_{D}", B=B, H=H, L=L, D=D)
+    q, k, v, _ = W.pass_inputs(w, 0, 0)
+    xq = W.normal(22, w, (B, L, H, D), 0, 0, 104)
+    Wq, _, _ = W.feature_weights(w)
+    cs, sn = W.rope_tables(w)
+    S = W.normal(23, w, (B, H, D, D), 0, 0, 105, io_dtype="f32") * 0.2
+    x, Wg = W.gate_inputs(w, 0, 0)
+    Wg = Wg * 8.0
+    # gates: headwise [B, L, H] and scalar [B, L]
+    g = torch.empty((B, L, H), dtype=torch.float32, device="cuda")
+    gt = torch.empty((B, L), dtype=torch.float32, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    lib.arl2_gate_proj(dev(x), dev(Wg[:1].contiguous()), gt, heads=H)
+    y = torch.empty_like(xq, device="cuda")
+    lib.arl2_feature_map(dev(xq), dev(Wq), dev(cs), dev(sn), y)
+    torch.cuda.synchronize()
+    g_ref = oracle.gate_proj(to_np(x), to_np(Wg))
+    assert np.abs(to_np(g) - g_ref).max() <= 2e-6
+    assert np.abs(to_np(gt) - g_ref[..., 0]).max() <= 2e-6
+    y_ref = oracle.feature_map(to_np(xq), to_np(Wq), to_np(cs), to_np(sn))
+    assert rel_err(to_np(y), y_ref) <= 2.0 ** -8
+    # fused query map, with the oracle's own gates
+    out = torch.empty_like(q, device="cuda")
+    g32 = torch.from_numpy(g_ref.astype(np.float32))
+    lib.arl2_hybrid_attn_fwd_fm(dev(q), dev(k), dev(v), dev(xq), dev(Wq), dev(cs), dev(sn), dev(S), dev(g32), out)
+    torch.cuda.synchronize()
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), g_ref.astype(np.float32),
+                     q_lin=to_np(_bf16_round(y_ref)))
+    e = rel_err(to_np(out), ref)
+    assert e <= TOL_BF16_OUT, f"fused map {B}x{H}x{L}x{D}: {e:.3e}"
