@@ -22,7 +22,8 @@
  *
  *   arl2_feature_map       the learned per-head maps and RoPE of Eq. (3) for the linear branch;
  *   arl2_hybrid_attn_fwd_ex  the readout pass with the linear branch's own query;
- *   arl2_gate_proj         the headwise gate G = sigmoid(x W_g) of Eq. (6).
+ *   arl2_hybrid_attn_fwd_fm  the readout pass that computes that query itself (fused feature map);
+ *   arl2_gate_proj         the gate G = sigmoid(x W_g) of Eq. (6), headwise or one per token.
  *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
@@ -38,7 +39,8 @@
  * Layouts (row-major):
  *   q, out      [B][Lq ][H][D]   io_dtype
  *   k, v        [B][Lkv][H][D]   io_dtype
- *   g           [B][Lq ][H]      g_dtype, values in [0,1]      (branch-mix gate, Eq. (6))
+ *   g           [B][Lq ][H]      g_dtype, values in [0,1]      (branch-mix gate, Eq. (6); other
+ *                                granularities: see arl2_gate_mode)
  *   S           [B][H][D][D]     fp32, S[d_k][d_v]; readout contracts d_k
  *   gate        [B][H]           fp32                          (forget gate alpha, Eq. (4))
  */
