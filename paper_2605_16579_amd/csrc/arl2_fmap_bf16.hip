@@ -9,11 +9,11 @@
 // so that a lane ends up with one token's outputs, four consecutive features per register quad: the
 // two members of every rotation pair sit in the same lane.
 //
-// One workgroup owns four consecutive heads (wavefront = head) and one to four tiles of 32 tokens
-// (four when there are enough workgroups to fill the chip several times over).  The
+// One workgroup owns four consecutive heads (wavefront = head) and one or more tiles of 32 tokens
+// (as many as it takes to run the launch as one round of two workgroups per CU, at most 16).  The
 // rows of four heads are 4 D contiguous bf16 per token, so the tile moves between HBM and LDS in
 // whole 1 KB rows (D = 128); the rotation table of the tile, which all heads share, is staged once per
-// tile.  Each wavefront keeps its head's W as MFMA A-operand fragments in registers for all four tiles,
+// tile.  Each wavefront keeps its head's W as MFMA A-operand fragments in registers for all its tiles,
 // reads its x fragments (B operand) from the LDS tile, and writes its rotated outputs back into the
 // same tile, which then leaves as whole rows.
 #include "arl2_device.h"
@@ -24,7 +24,7 @@ namespace {
 constexpr int NT = 256;    // four wavefronts = four heads
 constexpr int HG = 4;      // heads per workgroup
 constexpr int TT = 32;     // tokens per tile
-constexpr int MAX_NTILE = 4;   // most tiles per workgroup (W stays in registers across them)
+constexpr int MAX_NTILE = 16;  // most tiles per workgroup (W stays in registers across them)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
@@ -159,8 +159,11 @@ hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream)
 {
     const int n_hg = (a.H + HG - 1) / HG;
     const int tiles = (a.L + TT - 1) / TT;
-    // more tiles per workgroup amortise the W fragments, fewer give more workgroups: keep about 3 per CU
-    long long ntile = (long long)a.B * n_hg * tiles / 768;
+    // Two workgroups fit a CU (registers: W stays in them).  Up to that many workgroups run as one round,
+    // each walking as many tiles as that takes; beyond MAX_NTILE tiles per workgroup there are enough
+    // rounds for the last, partly filled one not to matter.
+    const long long slots = 2 * kNumCu;
+    long long ntile = ((long long)a.B * n_hg * tiles + slots - 1) / slots;
     if (ntile < 1) ntile = 1;
     if (ntile > MAX_NTILE) ntile = MAX_NTILE;
     const int n_ranges = (tiles + (int)ntile - 1) / (int)ntile;
