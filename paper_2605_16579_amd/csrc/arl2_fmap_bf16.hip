@@ -31,7 +31,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <int D>
+// PIPE: the x rows of the next tile are requested while the current one is computed (for workgroups that
+// walk several tiles; with a single tile the extra live registers only cost: 8 spill at D = 128).
+template <int D, bool PIPE>
 __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ranges, int n_hg, int ntile)
 {
     constexpr int KS = D / 16, EB = D / 32, CPR = D / 8;
@@ -64,6 +66,27 @@ __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ra
     const __amdgpu_buffer_rsrc_t c_rsrc = make_rsrc(rope ? a.cs : a.x, rope ? tab_bytes : 0);
     const __amdgpu_buffer_rsrc_t s_rsrc = make_rsrc(rope ? a.sn : a.x, rope ? tab_bytes : 0);
 
+    // chunk i of this thread in a tile: token tk, 16-byte column col of the token's HG heads
+    const uint32_t head0_bytes = (uint32_t)hg * HG * D * 2;
+    // Loads of one tile's x rows into registers; a tile past the end of the chunk reads nothing (every
+    // offset out of range).  The first tile is requested before the W fragments and every further tile
+    // while the one before it is being computed.  (The rotation table rows, small and L2-resident, are
+    // read when the tile is staged: holding them in registers too spills.)
+    u32x4 xr[XCH];
+    auto fetch_tile = [&](int tile) {
+        const int l0 = (rng * ntile + tile) * TT;
+        const bool live = tile < ntile && l0 < L;
+#pragma unroll
+        for (int i = 0; i < XCH; ++i) {
+            const int id = tid + NT * i;
+            const int tk = id / (HG * CPR), col = id % (HG * CPR);
+            const bool ok = live && l0 + tk < L && hg * HG + col / CPR < H;
+            const uint32_t off = ok ? ((uint32_t)b * L + l0 + tk) * tok_bytes + head0_bytes + 16 * col : total;
+            xr[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0);
+        }
+    };
+    if constexpr (PIPE) fetch_tile(0);
+
     // A operand: lane (row e = 32 eb + c, hh) holds W[h][e][16 t + 8 hh + 0..7], kept for all tiles
     bf16x8 wf[EB][KS];
     if (active) {
@@ -74,20 +97,16 @@ __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ra
             for (int t = 0; t < KS; ++t) wf[eb][t] = *(const bf16x8 *)(Wg + (size_t)32 * eb * D + 16 * t);
     }
 
-    // chunk i of this thread in a tile: token tk, 16-byte column col of the token's HG heads
-    const uint32_t head0_bytes = (uint32_t)hg * HG * D * 2;
     for (int tile = 0; tile < ntile; ++tile) {
         const int l0 = (rng * ntile + tile) * TT;
         if (l0 >= L) break;                              // uniform over the workgroup
         // ---- stage the x tile and the table tile
+        if constexpr (!PIPE) fetch_tile(tile);
 #pragma unroll
         for (int i = 0; i < XCH; ++i) {
             const int id = tid + NT * i;
             const int tk = id / (HG * CPR), col = id % (HG * CPR);
-            const bool ok = l0 + tk < L && hg * HG + col / CPR < H;
-            const uint32_t off = ok ? ((uint32_t)b * L + l0 + tk) * tok_bytes + head0_bytes + 16 * col : total;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0);
-            *(u32x4 *)(smem + tk * TROW + (col / CPR) * HROW + 16 * (col % CPR)) = v;
+            *(u32x4 *)(smem + tk * TROW + (col / CPR) * HROW + 16 * (col % CPR)) = xr[i];
         }
         if (rope) {
 #pragma unroll
@@ -105,6 +124,7 @@ __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ra
             }
         }
         __syncthreads();
+        if constexpr (PIPE) fetch_tile(tile + 1);        // in flight during this tile's arithmetic
         // ---- B operand: lane (token c, hh) holds x[l0 + c][h][16 t + 8 hh + 0..7]
         bf16x8 xf[KS];
         unsigned char *mine = smem + c * TROW + wave * HROW;
@@ -171,10 +191,15 @@ hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream)
     if (nwg <= 0 || nwg > 0x7fffffffLL) return hipErrorInvalidValue;
     // x and y are addressed with 32-bit byte offsets
     if ((long long)a.B * a.L * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.D == 128)
-        hipLaunchKernelGGL(feature_map_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_ranges, n_hg, (int)ntile);
+    const dim3 grid((unsigned)nwg), block(NT);
+    if (a.D == 128 && ntile > 1)
+        hipLaunchKernelGGL((feature_map_kernel<128, true>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
+    else if (a.D == 128)
+        hipLaunchKernelGGL((feature_map_kernel<128, false>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
+    else if (a.D == 64 && ntile > 1)
+        hipLaunchKernelGGL((feature_map_kernel<64, true>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
     else if (a.D == 64)
-        hipLaunchKernelGGL(feature_map_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a, n_ranges, n_hg, (int)ntile);
+        hipLaunchKernelGGL((feature_map_kernel<64, false>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
