@@ -724,11 +724,16 @@ def test_degenerate_rows(lib, oracle):
 
 # ---------------------------------------------------------------- stream capture
 
-def test_chunk_step_replays_from_a_captured_graph(lib):
+@pytest.mark.parametrize("long_chunk", [False, True])
+def test_chunk_step_replays_from_a_captured_graph(lib, long_chunk):
     """The library neither allocates nor synchronises, so a whole chunk step (readout passes, feature map,
     gate projection, all three commit rules) can be captured into a graph.  Every replay must reproduce the
-    eager result bit for bit, with eager work and synchronisations between the replays."""
+    eager result bit for bit, with eager work and synchronisations between the replays.  The long chunk
+    makes the token-sequential commit walk its blocks as several runs (three launches)."""
+    import dataclasses
     w = W.WORKLOADS["ragged_small"]
+    if long_chunk:
+        w = dataclasses.replace(w, name="graph_long", B=1, H=2, L=1700)
     q, k, v, g = (dev(t) for t in W.pass_inputs(w, 0, 0))
     kc, vc, gate = (dev(t) for t in W.clean_inputs(w, 0))
     alpha, beta_t = (dev(t) for t in W.token_gates(w, 0))
@@ -740,19 +745,20 @@ def test_chunk_step_replays_from_a_captured_graph(lib):
     ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
     ws_gdn = _gdn_ws(lib, w)
     S = S0.clone()
-    out, ql, gg = torch.empty_like(q), torch.empty_like(q), torch.empty_like(g)
+    out, out_fm, ql, gg = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty_like(g)
 
     def step():
         lib.arl2_gate_proj(xh, Wg, gg)
         lib.arl2_feature_map(q, Wq, cs, sn, ql)
         lib.arl2_hybrid_attn_fwd_ex(q, k, v, ql, S, gg, out)
+        lib.arl2_hybrid_attn_fwd_fm(q, k, v, q, Wq, cs, sn, S, gg, out_fm)
         lib.arl2_state_commit(kc, vc, gate, S, ws)
         lib.arl2_state_commit_delta(kc, vc, gate, beta, S, ws)
         lib.arl2_state_commit_gdn(kc, vc, alpha, beta_t, S, ws_gdn)
 
     step()                                               # eager reference: one step from S0
     torch.cuda.synchronize()
-    out_ref, S_ref = out.clone(), S.clone()
+    out_ref, fm_ref, S_ref = out.clone(), out_fm.clone(), S.clone()
 
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
@@ -764,10 +770,11 @@ def test_chunk_step_replays_from_a_captured_graph(lib):
     for _ in range(3):
         S.copy_(S0)                                      # eager work between the replays
         out.zero_()
+        out_fm.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(out, out_ref) and torch.equal(S, S_ref)
+        assert torch.equal(out, out_ref) and torch.equal(out_fm, fm_ref) and torch.equal(S, S_ref)
 
 
 def test_bench_stack_report_runs(lib):
