@@ -811,6 +811,15 @@ def test_shape_sweep(lib, oracle, B, H, L, D):
     out = gpu_fwd(lib, q, k, v, S0, g)
     e = rel_err(to_np(out), oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g)))
     assert e <= TOL_BF16_OUT, f"readout {B}x{H}x{L}x{D}: {e:.3e}"
+    # a softmax-only layer over a longer key range (cached tokens ahead of the chunk's own), no state
+    extra = [0, 1, 63, 64, 200][(B + H + L) % 5]
+    wk = dataclasses.replace(w, name=w.name + "_kv", L=L + extra)
+    _, k2, v2, _ = W.pass_inputs(wk, 0, 1)
+    out2 = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k2), dev(v2), None, None, out2)
+    torch.cuda.synchronize()
+    e = rel_err(to_np(out2), oracle.fwd(to_np(q), to_np(k2), to_np(v2), None, None))
+    assert e <= TOL_BF16_OUT, f"softmax over {L + extra} keys {B}x{H}x{L}x{D}: {e:.3e}"
     kc, vc, gate = W.clean_inputs(w, 0)
     S_dev = dev(S0).clone()
     gpu_commit(lib, kc, vc, gate, S_dev)
