@@ -18,6 +18,8 @@
 // same tile, which then leaves as whole rows.
 #include "arl2_device.h"
 
+#include <type_traits>
+
 namespace arl2 {
 namespace {
 
@@ -25,6 +27,15 @@ constexpr int NT = 256;    // four wavefronts = four heads
 constexpr int HG = 4;      // heads per workgroup
 constexpr int TT = 32;     // tokens per tile
 constexpr int MAX_NTILE = 16;  // most tiles per workgroup (W stays in registers across them)
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
@@ -87,15 +98,39 @@ __global__ __launch_bounds__(NT, 2) void feature_map_kernel(FmapArgs a, int n_ra
     };
     if constexpr (PIPE) fetch_tile(0);
 
-    // A operand: lane (row e = 32 eb + c, hh) holds W[h][e][16 t + 8 hh + 0..7], kept for all tiles
+    // A operand: lane (row e = 32 eb + c, hh) holds W[h][e][16 t + 8 hh + 0..7], kept for all tiles.
+    // The rows come in whole (16 lanes per 2 D-byte row) and pass, 32 rows at a time, through this
+    // wavefront's quarter of the still empty tile buffer; fragment loads straight from global memory touch
+    // 32 cache lines per instruction and are bound by cache-line requests.
     bf16x8 wf[EB][KS];
+    static_assert(HG * TT * HROW <= X_BYTES && TT * CPR % 64 == 0, "W staging uses the tile buffer");
     if (active) {
-        const bf16_t *Wg = (const bf16_t *)a.W + (size_t)h * D * D + (size_t)c * D + 8 * hh;
+        constexpr int WCH = TT * CPR / 64;               // 16-byte pieces of 32 rows per lane
+        const bf16_t *Wg = (const bf16_t *)a.W + (size_t)h * D * D;
+        unsigned char *wst = smem + wave * (TT * HROW);
+        u32x4 wr[2][WCH];
+        auto fetch_w = [&](auto eb_, auto buf_) {
+            constexpr int eb = decltype(eb_)::value, buf = decltype(buf_)::value;
 #pragma unroll
-        for (int eb = 0; eb < EB; ++eb)
+            for (int i = 0; i < WCH; ++i) {
+                const int id = lane + 64 * i;
+                wr[buf][i] = *(const u32x4 *)(Wg + (size_t)(32 * eb + id / CPR) * D + 8 * (id % CPR));
+            }
+        };
+        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        static_for<0, EB>([&](auto eb_) {
+            constexpr int eb = decltype(eb_)::value;
+            if constexpr (eb + 1 < EB) fetch_w(std::integral_constant<int, eb + 1>{}, std::integral_constant<int, (eb + 1) & 1>{});
 #pragma unroll
-            for (int t = 0; t < KS; ++t) wf[eb][t] = *(const bf16x8 *)(Wg + (size_t)32 * eb * D + 16 * t);
+            for (int i = 0; i < WCH; ++i) {
+                const int id = lane + 64 * i;
+                *(u32x4 *)(wst + (id / CPR) * HROW + 16 * (id % CPR)) = wr[eb & 1][i];
+            }
+#pragma unroll
+            for (int t = 0; t < KS; ++t) wf[eb][t] = *(const bf16x8 *)(wst + c * HROW + 32 * t + 16 * hh);
+        });
     }
+    __syncthreads();                                     // the tile buffer is free for the first tile
 
     for (int tile = 0; tile < ntile; ++tile) {
         const int l0 = (rng * ntile + tile) * TT;
