@@ -116,7 +116,7 @@ __device__ __forceinline__ void static_for(F &&f)
 enum ChainKind { kNone = 0, kS = 1, kPV = 2 };
 
 template <int D>
-__global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2)
+__global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2, int ragged_last)
 {
     using C = FwdCfg<D>;
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];
@@ -124,9 +124,26 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, c = lane & 31, hh = lane >> 5;
 
-    const int work = xcd_contiguous_id(blockIdx.x, gridDim.x);
-    const int qt = work % n_qtiles;
-    const int bh = work / n_qtiles;
+    int qt, bh;
+    if (ragged_last) {
+        // Several rounds of workgroups, and the last query tile of every head is ragged (its workgroup has
+        // idle wavefronts and finishes early): every XCD takes B H / 8 heads, their full tiles first, head
+        // by head, and their ragged tiles at the end of its dispatch order, where a short job shortens the
+        // last, partly filled round (workgroup ids go round the 8 XCDs in dispatch order).
+        const int x = blockIdx.x % kNumXcd, loc = blockIdx.x / kNumXcd;
+        const int heads_x = a.B * a.H / kNumXcd, n_full = n_qtiles - 1;
+        if (loc < heads_x * n_full) {
+            bh = x * heads_x + loc / n_full;
+            qt = loc % n_full;
+        } else {
+            bh = x * heads_x + (loc - heads_x * n_full);
+            qt = n_full;
+        }
+    } else {
+        const int work = xcd_contiguous_id(blockIdx.x, gridDim.x);
+        qt = work % n_qtiles;
+        bh = work / n_qtiles;
+    }
     const int h = bh % a.H, b = bh / a.H;
     const int H = a.H, Lq = a.Lq, Lkv = a.Lkv;
 
@@ -580,10 +597,12 @@ hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream)
     if ((long long)(a.Lkv + 4 * BN) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     const float scale_log2 = a.sm_scale * 1.4426950408889634f;
     const dim3 grid((unsigned)nwg), block(NT);
+    // more workgroups than CUs, a ragged last query tile per head, and whole heads per XCD
+    const int ragged_last = nwg > kNumCu && a.Lq % BM != 0 && n_qtiles > 1 && ((long long)a.B * a.H) % kNumXcd == 0;
     if (a.D == 128)
-        hipLaunchKernelGGL(fwd_bf16_kernel<128>, grid, block, 0, stream, a, n_qtiles, scale_log2);
+        hipLaunchKernelGGL(fwd_bf16_kernel<128>, grid, block, 0, stream, a, n_qtiles, scale_log2, ragged_last);
     else if (a.D == 64)
-        hipLaunchKernelGGL(fwd_bf16_kernel<64>, grid, block, 0, stream, a, n_qtiles, scale_log2);
+        hipLaunchKernelGGL(fwd_bf16_kernel<64>, grid, block, 0, stream, a, n_qtiles, scale_log2, ragged_last);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
