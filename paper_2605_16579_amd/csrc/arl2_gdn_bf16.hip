@@ -95,7 +95,16 @@ struct GdnCfg {
 __host__ __device__ constexpr size_t gdn_block_bytes(int D) { return (size_t)D * D * 8 + 16; }
 
 // ---- kernel 1: the affine map of one block of tokens -------------------------------------------------
-template <int D>
+// Workspace per block of tokens when the walk works on the operands of the solve instead of the composed
+// maps: Z^T hi, Z^T lo (bf16, A fragments: [32-feature block][16-token step][lane]), K (bf16, A fragments:
+// [32-token block][k-step][lane]), V^T (bf16, fragments [16-token step][32-column block][lane], tokens in
+// k-slot order = accumulator order), then beta_i, -beta_i gamma-_i r_i (fp32 [64] each) and gam.
+__host__ __device__ constexpr size_t gdn_ops_bytes(int D) { return (size_t)CT * D * 8 + 1024; }
+
+// OPS == false: the block's composed maps -E, Psi, gam.  OPS == true: the operands of its solve,
+//   S_out = gam S + Z^T (diag(beta) V + diag(-beta gamma- r) (K S)),    Z = (I + A)^-T diag(tail r) K,
+// half the bytes and none of the two D x D contractions; the walk then does two dependent contractions per block.
+template <int D, bool OPS>
 __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
 {
     using C = GdnCfg<D>;
@@ -329,7 +338,7 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
                 bf16x8 h8, l8;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float x = (e < 4 ? s0[e] : s1[e - 4]) * z[8 * q + e];
+                    const float x = (e < 4 ? s0[e] : s1[e - 4]) * z[8 * q + e];   // (sc == sc_one: times one)
                     h8[e] = to_bf16(x);
                     l8[e] = to_bf16(x - (float)h8[e]);
                 }
@@ -357,6 +366,39 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
             for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
     };
 
+    if constexpr (OPS) {
+        // sc_tr is no longer needed: it becomes an array of ones, so that put_z writes Z itself
+        if (tid < CT) sc_tr[tid] = 1.0f;
+        __syncthreads();
+        put_z(sc_tr);
+        __syncthreads();
+        unsigned char *rec = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_ops_bytes(D);
+        bf16x8 *Zhi = (bf16x8 *)rec, *Zlo = Zhi + CT * D / 8, *Kf = Zlo + CT * D / 8, *Vf = Kf + CT * D / 8;
+        float *scal = (float *)(rec + (size_t)CT * D * 8);
+        // Z^T: fragment (rb, t), lane (feature c32, hh) = Z^T[32 rb + c32][16 t + 8 hh + 0..7]
+        for (int p = tid; p < C::NB * 4 * 64; p += NTA) {
+            const int ln = p & 63, t = (p >> 6) & 3, rb = p >> 8;
+            const int off = (32 * rb + (ln & 31)) * C::ZROW + 2 * (16 * t + 8 * (ln >> 5));
+            Zhi[p] = *(const bf16x8 *)(R2 + off);
+            Zlo[p] = *(const bf16x8 *)(R3 + off);
+        }
+        // K: fragment (rbT, t), lane (token c32, hh) = K[32 rbT + c32][16 t + 8 hh + 0..7]
+        for (int p = tid; p < 2 * C::KS * 64; p += NTA) {
+            const int ln = p & 63, t = (p >> 6) % C::KS, rbT = p / (64 * C::KS);
+            Kf[p] = *(const bf16x8 *)(R0 + (32 * rbT + (ln & 31)) * C::ROW + 2 * (16 * t + 8 * (ln >> 5)));
+        }
+        // V^T: fragment (t, eblk), lane (column c32, hh) = V[16 t + 8 (j / 4) + 4 hh + j % 4][32 eblk + c32]
+        for (int f = wave; f < 4 * C::NB; f += NTA / 64) {
+            const int t = f / C::NB, eblk = f % C::NB;
+            Vf[f * 64 + lane] = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * eblk, 8 * C::ROW);
+        }
+        if (tid < CT) {
+            scal[tid] = sc_be[tid];
+            scal[CT + tid] = sc_se[tid];
+        }
+        if (tid == 0) scal[2 * CT] = sc_gam[0];
+        return;
+    }
     unsigned char *out = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_block_bytes(D);
     bf16x8 *Ehi = (bf16x8 *)out, *Elo = Ehi + D * D / 8;
     f32x4 *Psi = (f32x4 *)(out + (size_t)D * D * 4);
@@ -607,17 +649,250 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsign
     }
 }
 
+// ---- kernel 2': the walk on the operands of the solve --------------------------------------------------
+// One workgroup (four wavefronts) per 64 state columns; per block of tokens
+//   T = K S            [64 tokens x 64 columns], K raw bf16 against S hi + lo
+//   R = beta (.) V + (-beta gamma- r) (.) T      (fp32, then hi + lo)
+//   S <- gam S + Z^T R [D x 64], Z^T hi/lo against R hi/lo (three terms)
+// Wavefront w computes T and R for token block w & 1 and column block w >> 1, and updates the state rows
+// D/2 (w & 1) .. + D/2 of column block w >> 1.  S and R pass between the wavefronts through LDS ([column]
+// [row] and [column][token], 16-byte reads are B operands).  GROUPED as in the walk on composed maps; the
+// composite maps of the later runs are written in that walk's record format, which applies them.
+template <int D, bool GROUPED>
+__global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned char *recs, int nblk, int groups, unsigned char *gmaps)
+{
+    constexpr int KS = D / 16, NB = D / 32, NSL = D / 64, NRB = D / 64;   // k-steps, 32-blocks, 64-column slices, row blocks per wavefront
+    constexpr int SROW = 2 * D + 16, RROW = 2 * CT + 16;
+    constexpr int S_BYTES = 64 * SROW, R_BYTES = 64 * RROW;
+    constexpr int TROW = 2 * 64 + 16;                    // row of the [D][64] bf16 tile that transposes M_g
+    static_assert(2 * D * TROW <= 2 * S_BYTES + 2 * R_BYTES, "the transposing tiles reuse the exchange buffers");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S_BYTES + 2 * R_BYTES];
+    unsigned char *Shi = smem, *Slo = smem + S_BYTES, *Rhi = smem + 2 * S_BYTES, *Rlo = Rhi + R_BYTES;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
+    const int rbT = wave & 1, cb = wave >> 1, rbF0 = NRB * (wave & 1);
+    const int heads = a.B * a.H;
+    const int n_late = GROUPED ? (heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL : 0;
+    const bool late = (int)blockIdx.x < n_late;
+    const int id = late ? blockIdx.x : blockIdx.x - n_late;
+    const int xcd = id % kNumXcd, loc = id / kNumXcd;
+    const int units = late ? 2 * NSL : NSL;
+    const int unit = loc % units;
+    const int owner = (loc / units) * kNumXcd + xcd;
+    const int slice = unit % NSL;
+    const bool is_m = unit >= NSL;
+    int bh = owner, grp = 0, first = 0, n = nblk;
+    if constexpr (GROUPED) {
+        if (late) {
+            bh = owner / (groups - 1);
+            grp = 1 + owner % (groups - 1);
+        }
+        first = (int)((long long)grp * nblk / groups);
+        n = (int)((long long)(grp + 1) * nblk / groups) - first;
+    }
+    if (bh >= heads || n <= 0) return;
+    const int col = 32 * cb + c32, gcol = 64 * slice + col;          // column within the slice / within the state
+    float *Sg = a.S + (size_t)bh * D * D + gcol;
+
+    f32x16 s_acc[NRB];
+#pragma unroll
+    for (int i = 0; i < NRB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * (rbF0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+            if (!GROUPED || grp == 0) s_acc[i][r] = Sg[(size_t)row * D];
+            else s_acc[i][r] = (is_m && row == gcol) ? 1.0f : 0.0f;
+        }
+    const float v_on = is_m ? 0.0f : 1.0f;               // the identity's columns take no V term
+    float gprod = 1.0f;
+
+    const unsigned char *ws = recs + ((size_t)bh * nblk + first) * gdn_ops_bytes(D);
+    // Operands of a block are requested as soon as the registers of the block before are free: K, V^T and
+    // the per-token scalars once R is formed, Z^T once the state is updated; each then has the other
+    // contraction (about a thousand cycles) to arrive.
+    bf16x8 kf[KS], zh[NRB][4], zl[NRB][4], vf[2];
+    f32x4 be[4], se[4];
+    float gam_next = 1.0f, gam_cur;
+    auto fetch_kv = [&](int blk) __attribute__((always_inline)) {
+        const unsigned char *p = ws + (size_t)blk * gdn_ops_bytes(D);
+        const bf16x8 *Kf = (const bf16x8 *)p + 2 * (CT * D / 8), *Vf = Kf + CT * D / 8;
+        const float *scal = (const float *)(p + (size_t)CT * D * 8);
+        static_for<0, KS>([&](auto t_) { kf[decltype(t_)::value] = Kf[(rbT * KS + decltype(t_)::value) * 64 + lane]; });
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) vf[tt] = Vf[((2 * rbT + tt) * NB + 2 * slice + cb) * 64 + lane];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            be[q] = *(const f32x4 *)(scal + 32 * rbT + 8 * q + 4 * hh);
+            se[q] = *(const f32x4 *)(scal + CT + 32 * rbT + 8 * q + 4 * hh);
+        }
+        gam_next = scal[2 * CT];
+    };
+    auto fetch_z = [&](int blk) __attribute__((always_inline)) {
+        const bf16x8 *Zhi = (const bf16x8 *)(ws + (size_t)blk * gdn_ops_bytes(D)), *Zlo = Zhi + CT * D / 8;
+        static_for<0, NRB>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+            static_for<0, 4>([&](auto t_) {
+                constexpr int t = decltype(t_)::value;
+                zh[i][t] = Zhi[((rbF0 + i) * 4 + t) * 64 + lane];
+                zl[i][t] = Zlo[((rbF0 + i) * 4 + t) * 64 + lane];
+            });
+        });
+    };
+
+    fetch_kv(0);
+    fetch_z(0);
+#pragma unroll 1
+    for (int blk = 0; blk < n; ++blk) {
+        gam_cur = gam_next;
+        // past the last block this re-reads the last one (unused), which keeps the loop free of branches
+        const int nxt = blk + 1 < n ? blk + 1 : n - 1;
+        // ---- the state slice to LDS, [column][row], hi and lo
+        static_for<0, NRB>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 h4, l4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x = s_acc[i][4 * q + e];
+                    h4[e] = to_bf16(x);
+                    l4[e] = to_bf16(x - (float)h4[e]);
+                }
+                const int off = col * SROW + 2 * (32 * (rbF0 + i) + 8 * q + 4 * hh);
+                *(bf16x4 *)(Shi + off) = h4;
+                *(bf16x4 *)(Slo + off) = l4;
+            }
+        });
+        lds_barrier();                                   // (not __syncthreads: the operand loads stay in flight)
+        // ---- T = K S for this wavefront's 32 tokens x 32 columns
+        // (independent accumulator chains: a dependent MFMA waits ~50 cycles for its predecessor, an
+        // independent one issues after 32)
+        f32x16 t_h = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, t_l = t_h;
+        static_for<0, KS>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            const bf16x8 sh = *(const bf16x8 *)(Shi + col * SROW + 32 * t + 16 * hh);
+            const bf16x8 sl = *(const bf16x8 *)(Slo + col * SROW + 32 * t + 16 * hh);
+            t_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], sh, t_h, 0, 0, 0);
+            t_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], sl, t_l, 0, 0, 0);
+        });
+        // ---- R = beta V + (-beta gamma- r) T, register r <-> token 32 rbT + 8 (r / 4) + 4 hh + r % 4
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x4 h4, l4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int r = 4 * q + e;
+                const float v = (float)vf[r >> 3][r & 7];
+                const float x = fmaf(se[q][e], t_h[r] + t_l[r], GROUPED ? v_on * be[q][e] * v : be[q][e] * v);
+                h4[e] = to_bf16(x);
+                l4[e] = to_bf16(x - (float)h4[e]);
+            }
+            const int off = col * RROW + 2 * (32 * rbT + 8 * q + 4 * hh);
+            *(bf16x4 *)(Rhi + off) = h4;
+            *(bf16x4 *)(Rlo + off) = l4;
+        }
+        fetch_kv(nxt);
+        lds_barrier();
+        // ---- S <- gam S + Z^T R
+        bf16x8 rh[4], rl[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            rh[t] = *(const bf16x8 *)(Rhi + col * RROW + 32 * t + 16 * hh);
+            rl[t] = *(const bf16x8 *)(Rlo + col * RROW + 32 * t + 16 * hh);
+        }
+        f32x16 acc[NRB][3];
+        static_for<0, NRB>([&](auto i_) {
+            static_for<0, 3>([&](auto j_) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[decltype(i_)::value][decltype(j_)::value][r] = 0.f;
+            });
+        });
+        static_for<0, 4>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            static_for<0, NRB>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[i][t], rh[t], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[i][t], rl[t], acc[i][1], 0, 0, 0);
+                acc[i][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl[i][t], rh[t], acc[i][2], 0, 0, 0);
+            });
+        });
+        static_for<0, NRB>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_acc[i][r] = (fmaf(gam_cur, s_acc[i][r], acc[i][0][r]) + acc[i][1][r]) + acc[i][2][r];
+        });
+        fetch_z(nxt);
+        if constexpr (GROUPED) gprod *= gam_cur;
+    }
+
+    if (!GROUPED || grp == 0) {
+#pragma unroll
+        for (int i = 0; i < NRB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Sg[(size_t)(32 * (rbF0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3)) * D] = s_acc[i][r];
+        return;
+    }
+    if constexpr (GROUPED) {
+        // the composite map of run grp >= 1 as one record of the composed-map format
+        unsigned char *rec = gmaps + ((size_t)bh * (groups - 1) + grp - 1) * gdn_block_bytes(D);
+        if (!is_m) {                                     // c_g, accumulator order [row block][column block][quad][lane]
+#pragma unroll
+            for (int i = 0; i < NRB; ++i) {
+                f32x4 *Psi = (f32x4 *)(rec + (size_t)D * D * 4) + ((rbF0 + i) * NB + 2 * slice + cb) * 4 * 64 + lane;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    Psi[q * 64] = f32x4{s_acc[i][4 * q], s_acc[i][4 * q + 1], s_acc[i][4 * q + 2], s_acc[i][4 * q + 3]};
+            }
+            if (slice == 0 && tid == 0) *(float *)(rec + (size_t)D * D * 8) = gprod;
+            return;
+        }
+        // M_g - gam_g I, columns 64 slice .. + 63: through LDS into A-fragment order (lane = row, eight
+        // columns of k-steps 4 slice .. 4 slice + 3 in k-slot order), hi and lo parts
+        __syncthreads();                                 // the exchange buffers are no longer read
+        unsigned char *Thi = smem, *Tlo = smem + D * TROW;
+#pragma unroll
+        for (int i = 0; i < NRB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 32 * (rbF0 + i) + 8 * (r >> 2) + 4 * hh + (r & 3);
+                const float x = s_acc[i][r] - (row == gcol ? gprod : 0.0f);
+                const bf16_t h = to_bf16(x);
+                *(bf16_t *)(Thi + row * TROW + 2 * col) = h;
+                *(bf16_t *)(Tlo + row * TROW + 2 * col) = to_bf16(x - (float)h);
+            }
+        __syncthreads();
+        bf16x8 *Ehi = (bf16x8 *)rec, *Elo = Ehi + D * D / 8;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {                   // NB * 4 * 64 fragment pieces, 256 threads
+            const int p = tid + 256 * i;
+            const int ln = p & 63, tl = (p >> 6) & 3, rb = p >> 8;
+            const int off = (32 * rb + (ln & 31)) * TROW + 2 * (16 * tl + 4 * (ln >> 5));
+            const bf16x4 h0 = *(const bf16x4 *)(Thi + off), h1 = *(const bf16x4 *)(Thi + off + 16);
+            const bf16x4 l0 = *(const bf16x4 *)(Tlo + off), l1 = *(const bf16x4 *)(Tlo + off + 16);
+            const int idx = (rb * KS + 4 * slice + tl) * 64 + ln;
+            Ehi[idx] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+            Elo[idx] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+}
+
 }  // namespace
+
+#ifndef GDN_OPS
+#define GDN_OPS 1        // 1: the walk works on the operands of each block's solve; 0: on composed D x D maps
+#endif
 
 // Runs of blocks that are walked at the same time: as many as keep the walk within about one workgroup
 // per CU (the runs after the first cost twice the work), each at least four blocks long.
-static int gdn_groups(int B, int H, int nblk)
+static int gdn_groups(int B, int H, int nblk, int D)
 {
 #ifdef GDN_GROUPS
     int g = GDN_GROUPS;
 #else
     const long long heads = (long long)B * H;
-    int g = (int)((kNumCu / (heads * 4) + 1) / 2);       // (2 g - 1) * 4 slices * heads <= CUs
+    const int slices = GDN_OPS ? D / 64 : D / 32;        // workgroups per head and D columns
+    int g = (int)((kNumCu / (heads * slices) + 1) / 2);  // (2 g - 1) * slices * heads <= CUs
 #endif
     if (g > nblk / 4) g = nblk / 4;
     if (g > 8) g = 8;
@@ -627,32 +902,48 @@ static int gdn_groups(int B, int H, int nblk)
 size_t gdn_workspace_bytes(int B, int H, int L, int D)
 {
     const int nblk = (L + CT - 1) / CT;
-    return (size_t)B * H * (nblk + gdn_groups(B, H, nblk) - 1) * gdn_block_bytes(D);
+    const size_t per_block = GDN_OPS ? gdn_ops_bytes(D) : gdn_block_bytes(D);
+    return (size_t)B * H * (nblk * per_block + (gdn_groups(B, H, nblk, D) - 1) * gdn_block_bytes(D));
 }
 
 template <int D>
 static hipError_t launch_gdn(const GdnArgs &a, int nblk, unsigned nwg, hipStream_t stream)
 {
-    constexpr int NSL = D / 32;
     const int heads = a.B * a.H;
-    const int groups = gdn_groups(a.B, a.H, nblk);
+    const int groups = gdn_groups(a.B, a.H, nblk, D);
     const unsigned char *maps = (const unsigned char *)a.workspace;
-    unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * gdn_block_bytes(D);
-    hipLaunchKernelGGL(gdn_block_kernel<D>, dim3(nwg), dim3(NTA), 0, stream, a, nblk);
+    const size_t per_block = GDN_OPS ? gdn_ops_bytes(D) : gdn_block_bytes(D);
+    unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * per_block;
+    hipLaunchKernelGGL((gdn_block_kernel<D, GDN_OPS != 0>), dim3(nwg), dim3(NTA), 0, stream, a, nblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // whole owners per XCD: ceil(owners / 8) on each of the 8 XCDs
-    const unsigned nscan = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd * NSL);
+    const unsigned owners8 = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd);
+    const unsigned late8 = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd);
+    const unsigned nscan = owners8 * (D / 32);           // the walk on composed maps: 32 columns per workgroup
+#if GDN_OPS
+    constexpr int NSL = D / 64;
+    if (groups == 1) {
+        hipLaunchKernelGGL((gdn_walk_kernel<D, false>), dim3(owners8 * NSL), dim3(256), 0, stream, a, maps, nblk, 1,
+                           (unsigned char *)nullptr);
+        return hipGetLastError();
+    }
+    // the runs after the first (c and M slices), then the first runs (c slices)
+    hipLaunchKernelGGL((gdn_walk_kernel<D, true>), dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), 0, stream, a, maps, nblk,
+                       groups, gmaps);
+#else
+    constexpr int NSL = D / 32;
     if (groups == 1) {
         hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, maps, nblk, nblk, nblk, 1,
                            (unsigned char *)nullptr);
         return hipGetLastError();
     }
-    // the runs after the first (M and c slices), then the first runs (c slices), each padded to whole owners per XCD
-    const unsigned ngrp = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL) + nscan;
-    hipLaunchKernelGGL((gdn_scan_kernel<D, true>), dim3(ngrp), dim3(2 * D), 0, stream, a, maps, nblk, 0, nblk, groups, gmaps);
+    hipLaunchKernelGGL((gdn_scan_kernel<D, true>), dim3(late8 * 2 * NSL + nscan), dim3(2 * D), 0, stream, a, maps, nblk, 0, nblk,
+                       groups, gmaps);
+#endif
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    // the composite maps of the later runs, applied in order to what the first run left in S
     hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, (const unsigned char *)gmaps,
                        groups - 1, groups - 1, nblk, 1, (unsigned char *)nullptr);
     return hipGetLastError();

@@ -101,7 +101,7 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     # token-sequential variant: its own workspace size, per-token gates, bf16 inputs
     gdn = lambda d, alpha=0x3000, beta=0x5000: lib.arl2_state_commit_gdn(ctypes.byref(d), 0x1000, 0x2000, alpha, beta, 0x4000)
     need = A.arl2_gdn_workspace_bytes(1, 2, 64, 64)
-    assert need == 2 * (64 * 64 * 8 + 16)
+    assert need == 2 * (64 * 64 * 8 + 1024)               # two heads, one block of 64 tokens each: Z^T hi/lo, K, V^T, scalars
     assert A.arl2_gdn_workspace_bytes(1, 2, 65, 64) == 2 * need
     d.workspace_bytes = need - 1
     assert gdn(d) == 3                                    # one byte short
