@@ -205,8 +205,9 @@ arl2_status arl2_state_commit_delta(const arl2_desc *desc,
  *   beta      device fp32 [B][Lq][H], per-token learning rates; each step is a contraction for
  *             0 <= beta_j <= 1 and 0 <= alpha_j <= 1.
  *   S         device fp32 [B][H][D][D], updated IN PLACE.
- * desc->workspace must hold arl2_gdn_workspace_bytes(desc) bytes (the transition maps of all blocks
- * of 64 tokens and of up to 7 runs of blocks per head; about 128 KiB per map at D = 128).  Deterministic.
+ * desc->workspace must hold arl2_gdn_workspace_bytes(desc) bytes (per block of 64 tokens and head the
+ * operands of its transition, 65 KiB at D = 128, plus up to 7 composed D x D maps of 128 KiB per head).
+ * Deterministic.
  */
 size_t arl2_gdn_workspace_bytes(const arl2_desc *desc);
 arl2_status arl2_state_commit_gdn(const arl2_desc *desc,

@@ -4,27 +4,25 @@
 //
 // Only the state after the last token is wanted: every denoising pass reads the state as it stood
 // before the chunk (Sec. 3.3), so no per-token output exists.  That makes each block of 64 tokens a
-// single affine map of the state, and the maps of all blocks can be built independently of S:
+// single affine map of the state, whose ingredients can be built independently of S:
 //
 //   inside a block (gamma-_i = alpha_1..alpha_{i-1}, tail_i = alpha_{i+1}..alpha_64, gam = alpha_1..alpha_64)
 //     A_ij  = beta_i (alpha_{j+1}..alpha_{i-1}) k'_i.k'_j   for j < i, else 0      (unit lower triangular I + A)
 //     Z     = (I + A)^-T diag(tail) K'                       [64 x D]   back substitution
-//     E     = (diag(beta gamma-) Z)^T K'                     [D x D]
-//     Psi   = (diag(beta) Z)^T V                             [D x D]
-//     S_out = gam S_in - E S_in + Psi
+//     S_out = gam S_in + Z^T (diag(beta) V - diag(beta gamma-) K' S_in)
+//   (composed: S_out = gam S_in - E S_in + Psi with E = (diag(beta gamma-) Z)^T K', Psi = (diag(beta) Z)^T V)
 //
-// Kernel 1 (one workgroup per block of tokens, all blocks in parallel) builds -E (as bf16 hi + lo parts),
-// Psi (fp32) and gam.  The Gram matrix uses the raw bf16 keys (exact products) and is scaled in fp32;
-// the triangular solve runs in fp32 on the vector ALU, one thread per feature (right-looking, so the
-// 63 updates after each solved row are independent); the two contractions over tokens run on MFMA with
-// Z split into bf16 hi + lo against the raw bf16 K and V.  -E is computed transposed: the accumulator
-// registers of (-E)^T are then exactly the A-operand fragments of -E that kernel 2 needs (k-slot j of
-// half-wave hh <-> column 16 t + 8 (j / 4) + 4 hh + j % 4), and are stored as such, 16 bytes per lane.
-// Kernel 2 walks the blocks in order: one workgroup per (stream, head, 32 state columns), the state
-// slice in accumulator registers, S <- gam S + Psi + (-E) S with -E hi/lo against S hi/lo (three MFMA
-// terms, the lo x lo term is below fp32 rounding), the slice exchanged between wavefronts through LDS
-// in the same k-slot order.  With few heads the blocks of a head are cut into runs that are walked at
-// the same time, each later run producing its composite map, and a second launch applies those in order.
+// Kernel 1 (one workgroup per block of tokens, all blocks in parallel) builds Z and leaves it, with K, V^T
+// and the per-token scalars, in the workspace in the operand-fragment order of kernel 2.  The Gram matrix
+// uses the raw bf16 keys (exact products) and is scaled in fp32; the triangular solve runs in fp32 in
+// blocks of 16 tokens, the diagonal systems on the vector ALU (one thread per feature), the off-diagonal
+// updates on MFMA with hi + lo splits.
+// Kernel 2 walks the blocks in order, one workgroup per 64 state columns, with two dependent contractions
+// per block (K S, then Z^T R).  With few heads the blocks of a head are cut into runs that are walked at
+// the same time: the first run on the real state, every later run on the columns of the identity and on
+// zero, which yields its composite map (M_g, c_g); kernel 3 applies those D x D maps in order.
+// (A first version composed E and Psi per block in kernel 1 and walked on those: twice the workspace
+// traffic, which is what bounds the walk.)
 // All products of gates are formed by multiplication only, so gates of exactly zero are handled.
 #include "arl2_device.h"
 
@@ -83,28 +81,25 @@ struct GdnCfg {
     static constexpr int AST = 68;                      // floats per row of the 64 x 64 fp32 matrix
     static constexpr int NB = D / 32;                   // 32-wide blocks per side of a D x D matrix
     static constexpr int KS = D / 16;                   // k-steps of a D-long contraction
-    static constexpr int EPW = NB * NB / 4;             // output blocks per wavefront (all in one block row)
     static constexpr int REG = TILE > CT * AST * 4 ? TILE : CT * AST * 4;   // a region holds a tile or the fp32 matrix
     static constexpr int SC_OFF = 4 * REG;              // per-token scalars behind the four regions
     static constexpr int SMEM = SC_OFF + 8 * CT * 4 + 16;
     static_assert(D * ZROW <= REG, "a feature-major tile must fit into one region");
-    static_assert(KCH >= 1 && EPW >= 1, "unsupported head dimension");
+    static_assert(KCH >= 1, "unsupported head dimension");
 };
 
-// Workspace per block of tokens: -E hi, -E lo (bf16, fragment order), Psi (fp32, accumulator order), gam.
+// Bytes of a composed D x D map record: -E hi, -E lo (bf16, fragment order), Psi (fp32, accumulator order), gam.
 __host__ __device__ constexpr size_t gdn_block_bytes(int D) { return (size_t)D * D * 8 + 16; }
 
 // ---- kernel 1: the affine map of one block of tokens -------------------------------------------------
-// Workspace per block of tokens when the walk works on the operands of the solve instead of the composed
-// maps: Z^T hi, Z^T lo (bf16, A fragments: [32-feature block][16-token step][lane]), K (bf16, A fragments:
+// Workspace per block of tokens: Z^T hi, Z^T lo (bf16, A fragments: [32-feature block][16-token step][lane]), K (bf16, A fragments:
 // [32-token block][k-step][lane]), V^T (bf16, fragments [16-token step][32-column block][lane], tokens in
 // k-slot order = accumulator order), then beta_i, -beta_i gamma-_i r_i (fp32 [64] each) and gam.
 __host__ __device__ constexpr size_t gdn_ops_bytes(int D) { return (size_t)CT * D * 8 + 1024; }
 
-// OPS == false: the block's composed maps -E, Psi, gam.  OPS == true: the operands of its solve,
-//   S_out = gam S + Z^T (diag(beta) V + diag(-beta gamma- r) (K S)),    Z = (I + A)^-T diag(tail r) K,
-// half the bytes and none of the two D x D contractions; the walk then does two dependent contractions per block.
-template <int D, bool OPS>
+// Kernel 1: the operands of one block's solve,
+//   S_out = gam S + Z^T (diag(beta) V + diag(-beta gamma- r) (K S)),    Z = (I + A)^-T diag(tail r) K.
+template <int D>
 __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
 {
     using C = GdnCfg<D>;
@@ -347,135 +342,50 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
             }
         }
     };
-    // Operand fragments of 16-token step t.  A token-major tile is read through the transposing LDS read
-    // (k-slot j <-> token 16 t + 8 (j / 4) + 4 hh + j % 4); the feature-major Z^T tiles give the same order
-    // with two 8-byte reads.
-    const int dblk = (wave * C::EPW) / C::NB, eblk0 = (wave * C::EPW) % C::NB;
+    // A token-major tile is read through the transposing LDS read: lanes (column c32, hh) get eight tokens
+    // of their column, k-slot j <-> token 16 t + 8 (j / 4) + 4 hh + j % 4 (the order of accumulator registers).
     const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
-    const int z_off = (32 * dblk + c32) * C::ZROW + 8 * hh;
-    auto z_frag = [&](const unsigned char *Zt, int t) -> bf16x8 {
-        const bf16x4 lo = *(const bf16x4 *)(Zt + z_off + 32 * t);
-        const bf16x4 hi = *(const bf16x4 *)(Zt + z_off + 32 * t + 16);
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    };
-    f32x16 acc[C::EPW];
-    auto clear_acc = [&]() {
-#pragma unroll
-        for (int n = 0; n < C::EPW; ++n)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
-    };
 
-    if constexpr (OPS) {
-        // sc_tr is no longer needed: it becomes an array of ones, so that put_z writes Z itself
-        if (tid < CT) sc_tr[tid] = 1.0f;
-        __syncthreads();
-        put_z(sc_tr);
-        __syncthreads();
-        unsigned char *rec = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_ops_bytes(D);
-        bf16x8 *Zhi = (bf16x8 *)rec, *Zlo = Zhi + CT * D / 8, *Kf = Zlo + CT * D / 8, *Vf = Kf + CT * D / 8;
-        float *scal = (float *)(rec + (size_t)CT * D * 8);
-        // Z^T: fragment (rb, t), lane (feature c32, hh) = Z^T[32 rb + c32][16 t + 8 hh + 0..7]
-        for (int p = tid; p < C::NB * 4 * 64; p += NTA) {
-            const int ln = p & 63, t = (p >> 6) & 3, rb = p >> 8;
-            const int off = (32 * rb + (ln & 31)) * C::ZROW + 2 * (16 * t + 8 * (ln >> 5));
-            Zhi[p] = *(const bf16x8 *)(R2 + off);
-            Zlo[p] = *(const bf16x8 *)(R3 + off);
-        }
-        // K: fragment (rbT, t), lane (token c32, hh) = K[32 rbT + c32][16 t + 8 hh + 0..7]
-        for (int p = tid; p < 2 * C::KS * 64; p += NTA) {
-            const int ln = p & 63, t = (p >> 6) % C::KS, rbT = p / (64 * C::KS);
-            Kf[p] = *(const bf16x8 *)(R0 + (32 * rbT + (ln & 31)) * C::ROW + 2 * (16 * t + 8 * (ln >> 5)));
-        }
-        // V^T: fragment (t, eblk), lane (column c32, hh) = V[16 t + 8 (j / 4) + 4 hh + j % 4][32 eblk + c32]
-        for (int f = wave; f < 4 * C::NB; f += NTA / 64) {
-            const int t = f / C::NB, eblk = f % C::NB;
-            Vf[f * 64 + lane] = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * eblk, 8 * C::ROW);
-        }
-        if (tid < CT) {
-            scal[tid] = sc_be[tid];
-            scal[CT + tid] = sc_se[tid];
-        }
-        if (tid == 0) scal[2 * CT] = sc_gam[0];
-        return;
-    }
-    unsigned char *out = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_block_bytes(D);
-    bf16x8 *Ehi = (bf16x8 *)out, *Elo = Ehi + D * D / 8;
-    f32x4 *Psi = (f32x4 *)(out + (size_t)D * D * 4);
-    float *gam = (float *)(out + (size_t)D * D * 8);
-
-    // ---- 5. (-E)^T = K^T (-diag(beta gamma- r) Z): rows e (blocks eblk0 + n), columns d (block dblk)
-    put_z(sc_se);
+    // sc_tr is no longer needed: it becomes an array of ones, so that put_z writes Z itself
+    if (tid < CT) sc_tr[tid] = 1.0f;
     __syncthreads();
-    clear_acc();
-#pragma unroll
-    for (int t = 0; t < CT / 16; ++t) {
-        const bf16x8 zh = z_frag(R2, t), zl = z_frag(R3, t);
-#pragma unroll
-        for (int n = 0; n < C::EPW; ++n) {
-            const bf16x8 ka = lds_read_tr_pair(R0 + tr_off + 16 * t * C::ROW + 64 * (eblk0 + n), 8 * C::ROW);
-            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, zh, acc[n], 0, 0, 0);
-            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, zl, acc[n], 0, 0, 0);
-        }
+    put_z(sc_tr);
+    __syncthreads();
+    unsigned char *rec = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_ops_bytes(D);
+    bf16x8 *Zhi = (bf16x8 *)rec, *Zlo = Zhi + CT * D / 8, *Kf = Zlo + CT * D / 8, *Vf = Kf + CT * D / 8;
+    float *scal = (float *)(rec + (size_t)CT * D * 8);
+    // Z^T: fragment (rb, t), lane (feature c32, hh) = Z^T[32 rb + c32][16 t + 8 hh + 0..7]
+    for (int p = tid; p < C::NB * 4 * 64; p += NTA) {
+        const int ln = p & 63, t = (p >> 6) & 3, rb = p >> 8;
+        const int off = (32 * rb + (ln & 31)) * C::ZROW + 2 * (16 * t + 8 * (ln >> 5));
+        Zhi[p] = *(const bf16x8 *)(R2 + off);
+        Zlo[p] = *(const bf16x8 *)(R3 + off);
     }
-    // accumulator registers 8 tt .. 8 tt + 7 of block n are lane (d, hh)'s A fragment of -E for k-step 2 (eblk0 + n) + tt
-#pragma unroll
-    for (int n = 0; n < C::EPW; ++n)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            bf16x8 h8, l8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float x = acc[n][8 * tt + e];
-                h8[e] = to_bf16(x);
-                l8[e] = to_bf16(x - (float)h8[e]);
-            }
-            const int idx = (dblk * C::KS + 2 * (eblk0 + n) + tt) * 64 + lane;
-            Ehi[idx] = h8;
-            Elo[idx] = l8;
-        }
-    lds_barrier();                                       // every wavefront is done reading the Z^T tiles
-
-    // ---- 6. Psi = (diag(beta) Z)^T V: rows d (block dblk), columns e (blocks eblk0 + n)
-    put_z(sc_be);
-    lds_barrier();
-    clear_acc();
-#pragma unroll
-    for (int t = 0; t < CT / 16; ++t) {
-        const bf16x8 zh = z_frag(R2, t), zl = z_frag(R3, t);
-#pragma unroll
-        for (int n = 0; n < C::EPW; ++n) {
-            const bf16x8 vb = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * (eblk0 + n), 8 * C::ROW);
-            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, vb, acc[n], 0, 0, 0);
-            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, vb, acc[n], 0, 0, 0);
-        }
+    // K: fragment (rbT, t), lane (token c32, hh) = K[32 rbT + c32][16 t + 8 hh + 0..7]
+    for (int p = tid; p < 2 * C::KS * 64; p += NTA) {
+        const int ln = p & 63, t = (p >> 6) % C::KS, rbT = p / (64 * C::KS);
+        Kf[p] = *(const bf16x8 *)(R0 + (32 * rbT + (ln & 31)) * C::ROW + 2 * (16 * t + 8 * (ln >> 5)));
     }
-    // accumulator order of the scan kernel: [row block][column block][register quad][lane]
-#pragma unroll
-    for (int n = 0; n < C::EPW; ++n)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 x = {acc[n][4 * q], acc[n][4 * q + 1], acc[n][4 * q + 2], acc[n][4 * q + 3]};
-            Psi[((dblk * C::NB + eblk0 + n) * 4 + q) * 64 + lane] = x;
-        }
-    if (tid == 0) gam[0] = sc_gam[0];
+    // V^T: fragment (t, eblk), lane (column c32, hh) = V[16 t + 8 (j / 4) + 4 hh + j % 4][32 eblk + c32]
+    for (int f = wave; f < 4 * C::NB; f += NTA / 64) {
+        const int t = f / C::NB, eblk = f % C::NB;
+        Vf[f * 64 + lane] = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * eblk, 8 * C::ROW);
+    }
+    if (tid < CT) {
+        scal[tid] = sc_be[tid];
+        scal[CT + tid] = sc_se[tid];
+    }
+    if (tid == 0) scal[2 * CT] = sc_gam[0];
 }
 
-// ---- kernel 2: S <- gam S + Psi + (-E) S over the blocks in order ---------------------------------------
-// The same walk serves three purposes.
-//   GROUPED == false: one workgroup per (stream, head, 32 state columns) applies the `count` maps stored
-//     at `maps` (per head `head_stride` records apart) to the state in a.S.
-//   GROUPED == true: the blocks of a head are cut into `groups` runs of consecutive blocks that are walked
-//     at the same time.  Run 0 starts from the state in a.S and leaves X_0 there.  Every later run g
-//     computes its own composite map: the walk is applied to the columns of the identity (giving
-//     M_g = prod (gam_n I - E_n)) and to zero (giving c_g), 32 columns per workgroup, and the result is
-//     stored as one more record of the block format, -E := M_g - gam_g I with gam_g = prod gam_n (the
-//     multiple of the identity stays an exact fp32 scalar), Psi := c_g.  A second, ungrouped launch then
-//     applies the groups - 1 composite maps to X_0 in order.  For few heads this shortens the sequential
-//     chain from nblk steps to nblk / groups + groups - 1.
-template <int D, bool GROUPED>
-__global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsigned char *maps, int head_stride, int count,
-                                                          int nblk, int groups, unsigned char *gmaps)
+// ---- kernel 3: composed maps applied in order, S <- gam S + Psi + (-E) S ---------------------------------
+// One workgroup per (stream, head, 32 state columns) applies the `count` records stored at `maps` (per
+// head `count` records) to the state in a.S.  A record holds -E as bf16 hi + lo A fragments (k-slot j of
+// half-wave hh <-> column 16 t + 8 (j / 4) + 4 hh + j % 4), Psi in accumulator order and gam: the composite
+// maps that the walk below leaves for its runs of blocks.
+// Workspace per composed map: -E hi, -E lo (bf16, fragment order), Psi (fp32, accumulator order), gam.
+template <int D>
+__global__ __launch_bounds__(2 * D) void gdn_apply_kernel(GdnArgs a, const unsigned char *maps, int count)
 {
     constexpr int KS = D / 16;                           // k-steps of the D-long contraction
     constexpr int NSL = D / 32;                          // 32-column slices of the state
@@ -483,51 +393,26 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsign
     constexpr int SBUF = 32 * SROW;                      // one bf16 part of the 32-column slice, stored [column][row slot]
     constexpr int PFD = GDN_PFD, NBUF = PFD + 1;
     constexpr int EARLY = GDN_EARLY;                             // k-steps whose loads are issued before the MFMAs start
-    constexpr int TROW = 64 + 16;                        // LDS bytes per row of the [D][32] bf16 tile that transposes M_g
-    static_assert(2 * D * TROW <= 4 * SBUF, "the transposing tiles must fit into the exchange buffers");
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * SBUF];   // [buffer][hi, lo]
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
-    // Workgroups that read the same -E run on one XCD (consecutive workgroup ids go round the 8 XCDs), so
-    // that its L2 serves the re-reads: the slices of a head, or of a (head, run) pair.  The grid is padded
-    // to whole owners per XCD.  Grouped: the runs after the first (2 NSL workgroups each, M and c slices)
-    // come first in the grid, then the first runs (NSL workgroups each, c slices only), each kind dealt
-    // round the XCDs on its own, so that every XCD gets the same number of busy workgroups.
+    // The column slices of a head read the same -E: they run on one XCD (consecutive workgroup ids go
+    // round the 8 XCDs), so that its L2 serves the re-reads.  The grid is padded to whole heads per XCD.
     const int heads = a.B * a.H;
-    const int n_late = GROUPED ? (heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL : 0;
-    const bool late = (int)blockIdx.x < n_late;           // a run after the first
-    const int id = late ? blockIdx.x : blockIdx.x - n_late;   // n_late is a multiple of 8: the XCD phase is kept
-    const int xcd = id % kNumXcd, loc = id / kNumXcd;
-    const int units = late ? 2 * NSL : NSL;
-    const int unit = loc % units;
-    const int owner = (loc / units) * kNumXcd + xcd;     // head, or (head, later run) pair
-    const int slice = unit % NSL;
-    const bool is_m = unit >= NSL;
-    int bh = owner, grp = 0, first = 0, n = count;
-    if constexpr (GROUPED) {
-        if (late) {
-            bh = owner / (groups - 1);
-            grp = 1 + owner % (groups - 1);
-        }
-        first = (int)((long long)grp * nblk / groups);
-        n = (int)((long long)(grp + 1) * nblk / groups) - first;
-    }
+    const int xcd = blockIdx.x % kNumXcd, loc = blockIdx.x / kNumXcd;
+    const int slice = loc % NSL;
+    const int bh = (loc / NSL) * kNumXcd + xcd;
+    const int n = count;
     if (bh >= heads || n <= 0) return;
     float *Sg = a.S + (size_t)bh * D * D + 32 * slice + c32;
     const int row0 = 32 * wave + 4 * hh;                 // accumulator register r holds row row0 + 8 (r / 4) + r % 4
 
     f32x16 s_acc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 8 * (r >> 2) + (r & 3);
-        if (!GROUPED || grp == 0) s_acc[r] = Sg[(size_t)row * D];
-        else s_acc[r] = (is_m && row == 32 * slice + c32) ? 1.0f : 0.0f;
-    }
-    const float psi_on = is_m ? 0.0f : 1.0f;             // the identity's columns take no Psi
-    float gprod = 1.0f;                                  // gam of the blocks walked so far
+    for (int r = 0; r < 16; ++r) s_acc[r] = Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D];
 
-    const unsigned char *ws = maps + ((size_t)bh * head_stride + first) * gdn_block_bytes(D);
+    const unsigned char *ws = maps + (size_t)bh * count * gdn_block_bytes(D);
     // operands of the next PFD blocks are kept in flight (registers), a ring of NBUF = PFD + 1 buffers
     bf16x8 ehi[NBUF][KS], elo[NBUF][KS];
     f32x4 psi[NBUF][4];
@@ -590,11 +475,9 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsign
             if constexpr (t + EARLY < KS) fetch_part(nxt, nbuf, std::integral_constant<int, t + EARLY>{});
             __builtin_amdgcn_sched_barrier(0);
         });
-        const float psc = GROUPED ? psi_on : 1.0f;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            s_acc[r] = (fmaf(gam[buf], s_acc[r], psc * psi[buf][r >> 2][r & 3]) + acc0[r]) + (acc1[r] + acc2[r]);
-        if constexpr (GROUPED) gprod *= gam[buf];
+            s_acc[r] = (fmaf(gam[buf], s_acc[r], psi[buf][r >> 2][r & 3]) + acc0[r]) + (acc1[r] + acc2[r]);
     };
 
     static_for<0, PFD>([&](auto i_) { fetch(decltype(i_)::value < n ? decltype(i_)::value : n - 1, i_); });
@@ -606,58 +489,28 @@ __global__ __launch_bounds__(2 * D) void gdn_scan_kernel(GdnArgs a, const unsign
         if (blk + decltype(i_)::value < n) step(blk + decltype(i_)::value, i_);
     });
 
-    if (!GROUPED || grp == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D] = s_acc[r];
-        return;
-    }
-    if constexpr (GROUPED) {
-        // the composite map of run grp >= 1 as one record of the block format
-        unsigned char *rec = gmaps + ((size_t)bh * (groups - 1) + grp - 1) * gdn_block_bytes(D);
-        if (!is_m) {                                     // c_g, accumulator order: what the walk reads as Psi
-            f32x4 *Psi = (f32x4 *)(rec + (size_t)D * D * 4) + (wave * NSL + slice) * 4 * 64 + lane;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) Psi[q * 64] = f32x4{s_acc[4 * q], s_acc[4 * q + 1], s_acc[4 * q + 2], s_acc[4 * q + 3]};
-            if (slice == 0 && tid == 0) *(float *)(rec + (size_t)D * D * 8) = gprod;
-            return;
-        }
-        // M_g - gam_g I, columns 32 slice .. + 31: through LDS into A-fragment order (lane = row, eight
-        // columns of k-steps 2 slice, 2 slice + 1 in k-slot order), hi and lo parts
-        __syncthreads();                                 // the exchange buffers are no longer read
-        unsigned char *Thi = smem, *Tlo = smem + D * TROW;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = row0 + 8 * (r >> 2) + (r & 3);
-            const float x = s_acc[r] - (row == 32 * slice + c32 ? gprod : 0.0f);
-            const bf16_t h = to_bf16(x);
-            *(bf16_t *)(Thi + row * TROW + 2 * c32) = h;
-            *(bf16_t *)(Tlo + row * TROW + 2 * c32) = to_bf16(x - (float)h);
-        }
-        __syncthreads();
-        bf16x8 *Ehi = (bf16x8 *)rec, *Elo = Ehi + D * D / 8;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {                    // 4 D fragment pieces, 2 D threads
-            const int p = tid + 2 * D * i;
-            const int ln = p & 63, tl = (p >> 6) & 1, rb = p >> 7;
-            const int off = (32 * rb + (ln & 31)) * TROW + 2 * (16 * tl + 4 * (ln >> 5));
-            const bf16x4 h0 = *(const bf16x4 *)(Thi + off), h1 = *(const bf16x4 *)(Thi + off + 16);
-            const bf16x4 l0 = *(const bf16x4 *)(Tlo + off), l1 = *(const bf16x4 *)(Tlo + off + 16);
-            const int idx = (rb * KS + 2 * slice + tl) * 64 + ln;
-            Ehi[idx] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
-            Elo[idx] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
-    }
+    for (int r = 0; r < 16; ++r) Sg[(size_t)(row0 + 8 * (r >> 2) + (r & 3)) * D] = s_acc[r];
 }
 
-// ---- kernel 2': the walk on the operands of the solve --------------------------------------------------
+// ---- kernel 2: the walk on the operands of the solve ---------------------------------------------------
 // One workgroup (four wavefronts) per 64 state columns; per block of tokens
 //   T = K S            [64 tokens x 64 columns], K raw bf16 against S hi + lo
 //   R = beta (.) V + (-beta gamma- r) (.) T      (fp32, then hi + lo)
 //   S <- gam S + Z^T R [D x 64], Z^T hi/lo against R hi/lo (three terms)
 // Wavefront w computes T and R for token block w & 1 and column block w >> 1, and updates the state rows
 // D/2 (w & 1) .. + D/2 of column block w >> 1.  S and R pass between the wavefronts through LDS ([column]
-// [row] and [column][token], 16-byte reads are B operands).  GROUPED as in the walk on composed maps; the
-// composite maps of the later runs are written in that walk's record format, which applies them.
+// [row] and [column][token], 16-byte reads are B operands).
+//   GROUPED == false: one run, the whole chunk, on the state in a.S.
+//   GROUPED == true: the blocks of a head are cut into `groups` runs of consecutive blocks that are walked
+//     at the same time.  Run 0 starts from the state in a.S and leaves X_0 there.  Every later run g
+//     applies the walk to the columns of the identity (giving M_g = prod (gam_n I - E_n)) and to zero
+//     (giving c_g) and stores them as a composed-map record, -E := M_g - gam_g I with gam_g = prod gam_n
+//     (the multiple of the identity stays an exact fp32 scalar), Psi := c_g; kernel 3 then applies the
+//     groups - 1 records to X_0.  The chain shrinks from nblk steps to nblk / groups + groups - 1.
+//   The workgroups of a (head, run) pair read the same records: they run on one XCD (workgroup ids go round
+//   the 8 XCDs), the later runs first in the grid, the first runs after them, each kind dealt round the
+//   XCDs on its own so that every XCD gets the same number of busy workgroups.
 template <int D, bool GROUPED>
 __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned char *recs, int nblk, int groups, unsigned char *gmaps)
 {
@@ -708,45 +561,48 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
     float gprod = 1.0f;
 
     const unsigned char *ws = recs + ((size_t)bh * nblk + first) * gdn_ops_bytes(D);
-    // Operands of a block are requested as soon as the registers of the block before are free: K, V^T and
-    // the per-token scalars once R is formed, Z^T once the state is updated; each then has the other
-    // contraction (about a thousand cycles) to arrive.
-    bf16x8 kf[KS], zh[NRB][4], zl[NRB][4], vf[2];
-    f32x4 be[4], se[4];
-    float gam_next = 1.0f, gam_cur;
-    auto fetch_kv = [&](int blk) __attribute__((always_inline)) {
-        const unsigned char *p = ws + (size_t)blk * gdn_ops_bytes(D);
-        const bf16x8 *Kf = (const bf16x8 *)p + 2 * (CT * D / 8), *Vf = Kf + CT * D / 8;
+    // Two register sets per operand.  A set is refilled with the operands of the block after next as soon
+    // as it has been consumed (K after the first contraction, V^T and the per-token scalars after R, Z^T
+    // after the second contraction), so every load has almost two steps to arrive: the records are read
+    // once and come from HBM or the memory-side cache, about a step away.
+    bf16x8 kf[2][KS], zh[2][NRB][4], zl[2][NRB][4], vf[2][2];
+    f32x4 be[2][4], se[2][4];
+    float gam[2];
+    auto rec_of = [&](int blk) { return ws + (size_t)(blk < n ? blk : n - 1) * gdn_ops_bytes(D); };   // past the end: the last one again (unused)
+    auto fetch_k = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const bf16x8 *Kf = (const bf16x8 *)rec_of(blk) + 2 * (CT * D / 8);
+        static_for<0, KS>([&](auto t_) { kf[bi][decltype(t_)::value] = Kf[(rbT * KS + decltype(t_)::value) * 64 + lane]; });
+    };
+    auto fetch_v = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const unsigned char *p = rec_of(blk);
+        const bf16x8 *Vf = (const bf16x8 *)p + 3 * (CT * D / 8);
         const float *scal = (const float *)(p + (size_t)CT * D * 8);
-        static_for<0, KS>([&](auto t_) { kf[decltype(t_)::value] = Kf[(rbT * KS + decltype(t_)::value) * 64 + lane]; });
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) vf[tt] = Vf[((2 * rbT + tt) * NB + 2 * slice + cb) * 64 + lane];
+        for (int tt = 0; tt < 2; ++tt) vf[bi][tt] = Vf[((2 * rbT + tt) * NB + 2 * slice + cb) * 64 + lane];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            be[q] = *(const f32x4 *)(scal + 32 * rbT + 8 * q + 4 * hh);
-            se[q] = *(const f32x4 *)(scal + CT + 32 * rbT + 8 * q + 4 * hh);
+            be[bi][q] = *(const f32x4 *)(scal + 32 * rbT + 8 * q + 4 * hh);
+            se[bi][q] = *(const f32x4 *)(scal + CT + 32 * rbT + 8 * q + 4 * hh);
         }
-        gam_next = scal[2 * CT];
+        gam[bi] = scal[2 * CT];
     };
-    auto fetch_z = [&](int blk) __attribute__((always_inline)) {
-        const bf16x8 *Zhi = (const bf16x8 *)(ws + (size_t)blk * gdn_ops_bytes(D)), *Zlo = Zhi + CT * D / 8;
+    auto fetch_z = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const bf16x8 *Zhi = (const bf16x8 *)rec_of(blk), *Zlo = Zhi + CT * D / 8;
         static_for<0, NRB>([&](auto i_) {
             constexpr int i = decltype(i_)::value;
             static_for<0, 4>([&](auto t_) {
                 constexpr int t = decltype(t_)::value;
-                zh[i][t] = Zhi[((rbF0 + i) * 4 + t) * 64 + lane];
-                zl[i][t] = Zlo[((rbF0 + i) * 4 + t) * 64 + lane];
+                zh[bi][i][t] = Zhi[((rbF0 + i) * 4 + t) * 64 + lane];
+                zl[bi][i][t] = Zlo[((rbF0 + i) * 4 + t) * 64 + lane];
             });
         });
     };
-
-    fetch_kv(0);
-    fetch_z(0);
-#pragma unroll 1
-    for (int blk = 0; blk < n; ++blk) {
-        gam_cur = gam_next;
-        // past the last block this re-reads the last one (unused), which keeps the loop free of branches
-        const int nxt = blk + 1 < n ? blk + 1 : n - 1;
+    auto step = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const float gam_cur = gam[bi];
         // ---- the state slice to LDS, [column][row], hi and lo
         static_for<0, NRB>([&](auto i_) {
             constexpr int i = decltype(i_)::value;
@@ -773,9 +629,10 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
             constexpr int t = decltype(t_)::value;
             const bf16x8 sh = *(const bf16x8 *)(Shi + col * SROW + 32 * t + 16 * hh);
             const bf16x8 sl = *(const bf16x8 *)(Slo + col * SROW + 32 * t + 16 * hh);
-            t_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], sh, t_h, 0, 0, 0);
-            t_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], sl, t_l, 0, 0, 0);
+            t_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sh, t_h, 0, 0, 0);
+            t_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sl, t_l, 0, 0, 0);
         });
+        fetch_k(blk + 2, b_);
         // ---- R = beta V + (-beta gamma- r) T, register r <-> token 32 rbT + 8 (r / 4) + 4 hh + r % 4
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -783,8 +640,8 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int r = 4 * q + e;
-                const float v = (float)vf[r >> 3][r & 7];
-                const float x = fmaf(se[q][e], t_h[r] + t_l[r], GROUPED ? v_on * be[q][e] * v : be[q][e] * v);
+                const float v = (float)vf[bi][r >> 3][r & 7];
+                const float x = fmaf(se[bi][q][e], t_h[r] + t_l[r], GROUPED ? v_on * be[bi][q][e] * v : be[bi][q][e] * v);
                 h4[e] = to_bf16(x);
                 l4[e] = to_bf16(x - (float)h4[e]);
             }
@@ -792,7 +649,7 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
             *(bf16x4 *)(Rhi + off) = h4;
             *(bf16x4 *)(Rlo + off) = l4;
         }
-        fetch_kv(nxt);
+        fetch_v(blk + 2, b_);
         lds_barrier();
         // ---- S <- gam S + Z^T R
         bf16x8 rh[4], rl[4];
@@ -801,9 +658,9 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
             rh[t] = *(const bf16x8 *)(Rhi + col * RROW + 32 * t + 16 * hh);
             rl[t] = *(const bf16x8 *)(Rlo + col * RROW + 32 * t + 16 * hh);
         }
-        f32x16 acc[NRB][3];
+        f32x16 acc[NRB][2];                              // [0] hi x hi, [1] the two cross terms
         static_for<0, NRB>([&](auto i_) {
-            static_for<0, 3>([&](auto j_) {
+            static_for<0, 2>([&](auto j_) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[decltype(i_)::value][decltype(j_)::value][r] = 0.f;
             });
@@ -812,19 +669,31 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
             constexpr int t = decltype(t_)::value;
             static_for<0, NRB>([&](auto i_) {
                 constexpr int i = decltype(i_)::value;
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[i][t], rh[t], acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[i][t], rl[t], acc[i][1], 0, 0, 0);
-                acc[i][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl[i][t], rh[t], acc[i][2], 0, 0, 0);
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[bi][i][t], rh[t], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[bi][i][t], rl[t], acc[i][1], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl[bi][i][t], rh[t], acc[i][1], 0, 0, 0);
             });
         });
+        fetch_z(blk + 2, b_);
         static_for<0, NRB>([&](auto i_) {
             constexpr int i = decltype(i_)::value;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s_acc[i][r] = (fmaf(gam_cur, s_acc[i][r], acc[i][0][r]) + acc[i][1][r]) + acc[i][2][r];
+            for (int r = 0; r < 16; ++r) s_acc[i][r] = fmaf(gam_cur, s_acc[i][r], acc[i][0][r]) + acc[i][1][r];
         });
-        fetch_z(nxt);
         if constexpr (GROUPED) gprod *= gam_cur;
+    };
+
+    const std::integral_constant<int, 0> B0{};
+    const std::integral_constant<int, 1> B1{};
+    fetch_k(0, B0); fetch_v(0, B0); fetch_z(0, B0);
+    fetch_k(1, B1); fetch_v(1, B1); fetch_z(1, B1);
+    int blk = 0;
+#pragma unroll 1
+    for (; blk + 2 <= n; blk += 2) {
+        step(blk, B0);
+        step(blk + 1, B1);
     }
+    if (blk < n) step(blk, B0);
 
     if (!GROUPED || grp == 0) {
 #pragma unroll
@@ -879,10 +748,6 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
 
 }  // namespace
 
-#ifndef GDN_OPS
-#define GDN_OPS 1        // 1: the walk works on the operands of each block's solve; 0: on composed D x D maps
-#endif
-
 // Runs of blocks that are walked at the same time: as many as keep the walk within about one workgroup
 // per CU (the runs after the first cost twice the work), each at least four blocks long.
 static int gdn_groups(int B, int H, int nblk, int D)
@@ -891,8 +756,7 @@ static int gdn_groups(int B, int H, int nblk, int D)
     int g = GDN_GROUPS;
 #else
     const long long heads = (long long)B * H;
-    const int slices = GDN_OPS ? D / 64 : D / 32;        // workgroups per head and D columns
-    int g = (int)((kNumCu / (heads * slices) + 1) / 2);  // (2 g - 1) * slices * heads <= CUs
+    int g = (int)((kNumCu / (heads * (D / 64)) + 1) / 2);   // (2 g - 1) * D / 64 slices * heads <= CUs
 #endif
     if (g > nblk / 4) g = nblk / 4;
     if (g > 8) g = 8;
@@ -902,50 +766,36 @@ static int gdn_groups(int B, int H, int nblk, int D)
 size_t gdn_workspace_bytes(int B, int H, int L, int D)
 {
     const int nblk = (L + CT - 1) / CT;
-    const size_t per_block = GDN_OPS ? gdn_ops_bytes(D) : gdn_block_bytes(D);
-    return (size_t)B * H * (nblk * per_block + (gdn_groups(B, H, nblk, D) - 1) * gdn_block_bytes(D));
+    return (size_t)B * H * (nblk * gdn_ops_bytes(D) + (gdn_groups(B, H, nblk, D) - 1) * gdn_block_bytes(D));
 }
 
 template <int D>
 static hipError_t launch_gdn(const GdnArgs &a, int nblk, unsigned nwg, hipStream_t stream)
 {
+    constexpr int NSL = D / 64;
     const int heads = a.B * a.H;
     const int groups = gdn_groups(a.B, a.H, nblk, D);
-    const unsigned char *maps = (const unsigned char *)a.workspace;
-    const size_t per_block = GDN_OPS ? gdn_ops_bytes(D) : gdn_block_bytes(D);
-    unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * per_block;
-    hipLaunchKernelGGL((gdn_block_kernel<D, GDN_OPS != 0>), dim3(nwg), dim3(NTA), 0, stream, a, nblk);
+    const unsigned char *recs = (const unsigned char *)a.workspace;
+    unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * gdn_ops_bytes(D);
+    hipLaunchKernelGGL(gdn_block_kernel<D>, dim3(nwg), dim3(NTA), 0, stream, a, nblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // whole owners per XCD: ceil(owners / 8) on each of the 8 XCDs
     const unsigned owners8 = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd);
-    const unsigned late8 = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd);
-    const unsigned nscan = owners8 * (D / 32);           // the walk on composed maps: 32 columns per workgroup
-#if GDN_OPS
-    constexpr int NSL = D / 64;
     if (groups == 1) {
-        hipLaunchKernelGGL((gdn_walk_kernel<D, false>), dim3(owners8 * NSL), dim3(256), 0, stream, a, maps, nblk, 1,
+        hipLaunchKernelGGL((gdn_walk_kernel<D, false>), dim3(owners8 * NSL), dim3(256), 0, stream, a, recs, nblk, 1,
                            (unsigned char *)nullptr);
         return hipGetLastError();
     }
     // the runs after the first (c and M slices), then the first runs (c slices)
-    hipLaunchKernelGGL((gdn_walk_kernel<D, true>), dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), 0, stream, a, maps, nblk,
+    const unsigned late8 = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd);
+    hipLaunchKernelGGL((gdn_walk_kernel<D, true>), dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), 0, stream, a, recs, nblk,
                        groups, gmaps);
-#else
-    constexpr int NSL = D / 32;
-    if (groups == 1) {
-        hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, maps, nblk, nblk, nblk, 1,
-                           (unsigned char *)nullptr);
-        return hipGetLastError();
-    }
-    hipLaunchKernelGGL((gdn_scan_kernel<D, true>), dim3(late8 * 2 * NSL + nscan), dim3(2 * D), 0, stream, a, maps, nblk, 0, nblk,
-                       groups, gmaps);
-#endif
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     // the composite maps of the later runs, applied in order to what the first run left in S
-    hipLaunchKernelGGL((gdn_scan_kernel<D, false>), dim3(nscan), dim3(2 * D), 0, stream, a, (const unsigned char *)gmaps,
-                       groups - 1, groups - 1, nblk, 1, (unsigned char *)nullptr);
+    hipLaunchKernelGGL(gdn_apply_kernel<D>, dim3(owners8 * (D / 32)), dim3(2 * D), 0, stream, a, (const unsigned char *)gmaps,
+                       groups - 1);
     return hipGetLastError();
 }
 
