@@ -148,6 +148,9 @@ def main() -> int:
     ap.add_argument("--gate-proj", action="store_true",
                     help="compute the mix gate of every readout pass on the path, G = sigmoid(x W_g) (arl2_gate_proj), "
                          "instead of taking it as an input.  Not the headline configuration.")
+    ap.add_argument("--gate-granularity", choices=["head", "token", "element"], default="head",
+                    help="with --gate-proj: one gate per (token, head) (the paper's choice), per token, or per output "
+                         "feature (W_g is d_model x d_model: a dense product), the three rows of the gate ablation")
     ap.add_argument("--clean-readout", action="store_true",
                     help="one more readout pass per step, on the clean pass's inputs before the commit "
                          "(passes + 1 readouts, then the commit).  Not the headline configuration.")
@@ -213,7 +216,10 @@ def main() -> int:
         if w.io_dtype != "bf16":
             print("bench.py: --gate-proj needs a bf16 workload", file=sys.stderr)
             return 2
-        gp = [tuple(t.to(dev) for t in W.gate_inputs(w, 0, p)) for p in range(w.passes)]
+        n_gate = {"head": w.H, "token": 1, "element": w.H * w.D}[args.gate_granularity]
+        g_shape = {"head": (w.B, w.L, w.H), "token": (w.B, w.L), "element": (w.B, w.L, w.H, w.D)}[args.gate_granularity]
+        gp = [tuple(t.to(dev) for t in W.gate_inputs(w, 0, p, n_out=n_gate)) +
+              (torch.empty(g_shape, dtype=torch.float32, device=dev),) for p in range(w.passes)]
     n_read = w.passes + (1 if args.clean_readout else 0)
     fm = None
     if args.feature_maps:
@@ -256,7 +262,8 @@ def main() -> int:
         for p in range(n_read):
             q, k, v, g = passes[p % w.passes]
             if gp is not None:
-                A.arl2_gate_proj(gp[p % w.passes][0], gp[p % w.passes][1], g)
+                xg, Wg, g = gp[p % w.passes]
+                A.arl2_gate_proj(xg, Wg, g, heads=w.H)
             if fm is not None:
                 if args.unfused_maps:
                     A.arl2_feature_map(q, fm["Wq"], fm["cs"], fm["sn"], fm["ql"])
@@ -304,7 +311,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "commit_rule": rule, "feature_maps": ("fused query map" if not args.unfused_maps else "separate launches") if args.feature_maps else False, "gate_proj": bool(args.gate_proj),
+                   "passes": w.passes, "commit_rule": rule, "feature_maps": ("fused query map" if not args.unfused_maps else "separate launches") if args.feature_maps else False, "gate_proj": args.gate_granularity if args.gate_proj else False,
                    "readouts_per_step": n_read, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,

@@ -23,7 +23,7 @@
  *   arl2_feature_map       the learned per-head maps and RoPE of Eq. (3) for the linear branch;
  *   arl2_hybrid_attn_fwd_ex  the readout pass with the linear branch's own query;
  *   arl2_hybrid_attn_fwd_fm  the readout pass that computes that query itself (fused feature map);
- *   arl2_gate_proj         the gate G = sigmoid(x W_g) of Eq. (6), headwise or one per token.
+ *   arl2_gate_proj         the gate G = sigmoid(x W_g) of Eq. (6): headwise, one per token or element-wise.
  *
  * Reading of the feature map: q and k arrive after RoPE, the learned 1x1 maps are
  * the identity, so phi is the L2 normalisation over the head dimension,
@@ -156,12 +156,13 @@ arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W
  * Branch-mix gate, paper Eq. (6): G = sigmoid(x W_g), the g argument of the readout pass.
  *   x         device bf16 [B][Lq][H*D], the layer's hidden state (desc->io_dtype must be ARL2_BF16).
  *   Wg        device bf16 [n][H*D], one row per gate output: n = H for desc->g_mode == ARL2_GATE_PER_HEAD
- *             (row h is column h of the paper's (H*D) x H matrix W_g), n = 1 for ARL2_GATE_PER_TOKEN
- *             (the scalar gate of the paper's gate ablation, Tab. 4).
- *   g         device [B][Lq][n] in desc->g_dtype, fully overwritten; must not alias an input.
- * Up to 32 heads.  fp32 accumulation and sigmoid.  ARL2_GATE_PER_ELEMENT returns ARL2_ERR_UNSUPPORTED:
- * that projection is a dense (H*D) x (H*D) matrix product, a job for a BLAS library, whose output the
- * readout pass takes as it is.
+ *             (row h is column h of the paper's (H*D) x H matrix W_g), n = 1 for ARL2_GATE_PER_TOKEN and
+ *             n = H*D for ARL2_GATE_PER_ELEMENT (the scalar and the element-wise gate of the paper's gate
+ *             ablation, Tab. 4; row h*D + e is the gate of feature e of head h).  Below 2 GiB.
+ *   g         device [B][Lq][n] in desc->g_dtype ([B][Lq][H][D] element-wise), fully overwritten; must
+ *             not alias an input.
+ * fp32 accumulation and sigmoid.  Up to 32 outputs per token the call is bound by reading x once; beyond
+ * that it is a dense matrix product on the matrix cores.
  */
 arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg, void *g);
 

@@ -228,22 +228,24 @@ def arl2_gate_proj(x: torch.Tensor, Wg: torch.Tensor, g: torch.Tensor, *, heads:
                    stream: Optional[int] = None) -> None:
     """g = sigmoid(x Wg^T): the mix gate of Eq. (6).  x [B, L, H*D] bf16.  Headwise: Wg [H, H*D] bf16,
     g [B, L, H] fp32 or bf16 (written).  Scalar gate (one per token): Wg [1, H*D], g [B, L], and ``heads``
-    names H."""
+    names H.  Element-wise gate (one per feature): Wg [H*D, H*D], g [B, L, H, D]."""
     if x.dim() != 3 or Wg.dim() != 2:
-        raise ValueError("x must be [B, L, H*D] and Wg [H, H*D] or [1, H*D]")
+        raise ValueError("x must be [B, L, H*D] and Wg [H, H*D], [1, H*D] or [H*D, H*D]")
     B, L, dm = x.shape
-    scalar = g.dim() == 2
+    scalar, elem = g.dim() == 2, g.dim() == 4
     if scalar and heads is None:
         raise ValueError("a scalar gate needs the number of heads")
-    H = heads if heads is not None else Wg.shape[0]
+    H = heads if heads is not None else (g.shape[2] if elem else Wg.shape[0])
     if H < 1 or dm % H:
         raise ValueError("the hidden size must be a multiple of the number of heads")
     d = make_desc(B, H, L, L, dm // H, _dtype_code(x), _dtype_code(g), stream=stream)
     if scalar:
         d.g_mode = ARL2_GATE_PER_TOKEN
+    elif elem:
+        d.g_mode = ARL2_GATE_PER_ELEMENT
     st = load_library().arl2_gate_proj(ctypes.byref(d), _dev(x, "x"),
-                                       _dev(Wg, "Wg", (1 if scalar else H, dm), x.dtype),
-                                       _dev(g, "g", (B, L) if scalar else (B, L, H)))
+                                       _dev(Wg, "Wg", (1 if scalar else dm if elem else H, dm), x.dtype),
+                                       _dev(g, "g", (B, L) if scalar else (B, L, H, dm // H) if elem else (B, L, H)))
     _check(st)
 
 

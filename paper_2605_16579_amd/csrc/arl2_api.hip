@@ -177,16 +177,16 @@ arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg,
     if (reinterpret_cast<uintptr_t>(g) & 3u) return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
     if (g == x || g == Wg) return fail(ARL2_ERR_INVALID_ARG, "g must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj takes bf16 x, Wg only");
-    if (desc->H > 32) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj supports up to 32 heads");
-    if (desc->g_mode == ARL2_GATE_PER_ELEMENT)
-        return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj has no element-wise mode (a dense matrix product)");
     if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
+    const int n_out = desc->g_mode == ARL2_GATE_PER_TOKEN ? 1 : desc->g_mode == ARL2_GATE_PER_ELEMENT ? desc->H * desc->D : desc->H;
+    if (!fits_32bit((double)n_out * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "Wg must stay below 2 GiB");
 
     arl2::GateArgs a;
     a.x = x; a.Wg = Wg; a.g = g;
     a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.dm = desc->H * desc->D;
-    a.n_out = desc->g_mode == ARL2_GATE_PER_TOKEN ? 1 : desc->H;
+    a.n_out = n_out;
     a.g_is_bf16 = desc->g_dtype == ARL2_BF16;
     const hipError_t e = arl2::launch_gate_proj_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
     if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "gate projection launch failed: %s", hipGetErrorString(e));

@@ -57,10 +57,7 @@ __device__ __forceinline__ void static_for(F &&f)
 }
 
 constexpr int PFT = 3;     // tiles whose loads are in flight (register ring): HBM latency is several tile times
-#ifndef COMMIT_PFW
-#define COMMIT_PFW 3
-#endif
-constexpr int PFW = COMMIT_PFW;   // the same for the producer wavefronts of the plain commit, which hold no accumulators
+constexpr int PFW = 3;     // the same for the producer wavefronts of the plain commit, which hold no accumulators
 
 template <int D, bool DELTA>
 struct CommitCfg {

@@ -66,7 +66,7 @@ struct GateArgs {
     const void *Wg;        // [n_out][dm] bf16
     void *g;               // [B][L][n_out], fp32 or bf16
     int B, H, L, dm;
-    int n_out;             // gate outputs per token: H (headwise) or 1 (scalar)
+    int n_out;             // gate outputs per token: H (headwise), 1 (scalar) or H * D (element-wise)
     int g_is_bf16;
 };
 
@@ -124,6 +124,14 @@ __device__ __forceinline__ float lane_group_sum(float x)
     x += dpp_peek<0x141>(x);                 // row_half_mirror
     if constexpr (N == 16) x += dpp_peek<0x140>(x);   // row_mirror
     return x;
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads and stores issued before it stay in
+// flight (__syncthreads would first wait for all of them to complete, which cancels a register prefetch
+// that runs several tiles ahead).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // 1 / sqrt(x) in one hardware instruction (about 1 ulp); x > 0.

@@ -33,12 +33,8 @@ namespace {
 
 constexpr int CT = 64;     // tokens per block
 constexpr int NTA = 256;   // threads of the block kernel
-#ifndef GDN_PFD
-#define GDN_PFD 2        // blocks whose operands the scan keeps in flight
-#endif
-#ifndef GDN_EARLY
-#define GDN_EARLY 2      // k-steps of the next operands that the scan requests before its MFMAs start
-#endif
+constexpr int GDN_PFD = 2;    // blocks whose operands the scan keeps in flight
+constexpr int GDN_EARLY = 2;  // k-steps of the next operands that the scan requests before its MFMAs start
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
@@ -52,13 +48,6 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char *p, int s
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-// Workgroup barrier that orders LDS traffic only: global stores issued before it stay in flight
-// (__syncthreads would first wait for them to complete).
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <int I, int N, class F>
@@ -752,12 +741,8 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
 // per CU (the runs after the first cost twice the work), each at least four blocks long.
 static int gdn_groups(int B, int H, int nblk, int D)
 {
-#ifdef GDN_GROUPS
-    int g = GDN_GROUPS;
-#else
     const long long heads = (long long)B * H;
     int g = (int)((kNumCu / (heads * (D / 64)) + 1) / 2);   // (2 g - 1) * D / 64 slices * heads <= CUs
-#endif
     if (g > nblk / 4) g = nblk / 4;
     if (g > 8) g = 8;
     return g < 1 ? 1 : g;

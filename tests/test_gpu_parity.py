@@ -614,6 +614,81 @@ def test_gate_projection_small(lib, oracle, B, L, H, D, gdt):
     assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9), f"{err:.3e}"
 
 
+@pytest.mark.parametrize("B,L,H,D,n_out,gdt", [
+    (2, 200, 2, 64, 0, "f32"),        # element-wise, one output tile, two steps of the hidden dimension
+    (1, 333, 3, 64, 0, "bf16"),       # ragged token tile and ragged output tile, odd number of steps
+    (1, 130, 5, 64, 0, "f32"),        # three output tiles, five steps
+    (3, 77, 2, 128, 0, "f32"),        # fewer tokens than a tile per stream, tiles across streams
+    (1, 150, 40, 64, 40, "f32"),      # headwise with more heads than the skinny kernel takes
+])
+def test_gate_projection_dense(lib, oracle, B, L, H, D, n_out, gdt):
+    """More than 32 gate outputs per token (the element-wise gate, or very many heads): the dense kernel."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gated{H}x{D}", B=B, L=L, H=H, D=D)
+    elem = n_out == 0
+    x, Wg = W.gate_inputs(w, 0, 0, n_out=H * D if elem else n_out)
+    Wg = (Wg * 8.0).contiguous()
+    gdtype = torch.float32 if gdt == "f32" else torch.bfloat16
+    g = torch.full((B, L, H, D) if elem else (B, L, H), -1.0, dtype=gdtype, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    torch.cuda.synchronize()
+    ref = oracle.gate_proj(to_np(x), to_np(Wg)).reshape(g.shape)
+    assert ref.min() < 0.3 and ref.max() > 0.7
+    err = np.abs(to_np(g) - ref).max()
+    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9), f"{err:.3e}"
+
+
+@pytest.mark.parametrize("B,L,H,D,gdt", [
+    (3, 4400, 39, 64, "f32"),         # 52 x 10 tiles of 256 x 256: ragged last token tile, last output tile 192 wide
+    (8, 4680, 12, 128, "bf16"),       # the batched workload: 147 x 6 tiles
+])
+def test_gate_projection_dense_large_tiles(lib, oracle, B, L, H, D, gdt):
+    """Problems that fill the chip at least twice with 256 x 256 tiles take the large-tile kernel: sampled
+    tokens against the oracle, and every element written."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gatebig{H}x{D}", B=B, L=L, H=H, D=D)
+    dm = H * D
+    assert ((B * L + 255) // 256) * ((dm + 255) // 256) >= 512
+    x, Wg = W.gate_inputs(w, 0, 0, n_out=dm)
+    Wg = (Wg * 8.0).contiguous()
+    g = torch.full((B, L, H, D), -1.0, dtype=torch.float32 if gdt == "f32" else torch.bfloat16, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    torch.cuda.synchronize()
+    assert float(g.min()) > 0.0 and float(g.max()) < 1.0
+    rows = sample_rows(L, 24, seed=7, block=256)
+    ref = oracle.gate_proj(to_np(x)[:, rows], to_np(Wg)).reshape(B, len(rows), H, D)
+    err = np.abs(to_np(g)[:, rows] - ref).max()
+    # fp32 arithmetic: 2e-6; a bf16 gate adds its rounding, half an ulp below 1 = 2^-9
+    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9 + 2e-6), f"{err:.3e}"
+
+
+def test_elementwise_gate_projection_feeds_the_readout_full_size(lib, oracle):
+    """Headline shape: the element-wise gate G = sigmoid(x W_g), W_g 1536 x 1536, on the GPU against the
+    oracle on sampled tokens, then used as the readout's gate."""
+    w = W.WORKLOADS["wan_layer"]
+    dm = w.H * w.D
+    x, Wg = W.gate_inputs(w, 0, 0, n_out=dm)
+    g = torch.full((w.B, w.L, w.H, w.D), -1.0, dtype=torch.float32, device="cuda")
+    lib.arl2_gate_proj(dev(x), dev(Wg), g)
+    torch.cuda.synchronize()
+    rows = sample_rows(w.L, 48, seed=6)
+    g_ref = oracle.gate_proj(to_np(x)[:, rows], to_np(Wg)).reshape(w.B, len(rows), w.H, w.D)
+    err = np.abs(to_np(g)[:, rows] - g_ref).max()
+    print(f"[wan_layer] element-wise gate projection: max abs err {err:.3e}, gates in [{g_ref.min():.3f}, {g_ref.max():.3f}]", flush=True)
+    assert err <= 2e-6
+    assert float(g.min()) > 0.0 and float(g.max()) < 1.0          # every element was written
+    q, k, v, _ = W.pass_inputs(w, 0, 0)
+    S0 = W.normal(16, w, (w.B, w.H, w.D, w.D), 0, 0, 98, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S0), g, out)
+    torch.cuda.synchronize()
+    g_rows = np.full((w.B, w.L, w.H, w.D), 0.5, dtype=np.float32)
+    g_rows[:, rows] = g_ref.astype(np.float32)
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S0).astype(np.float64), g_rows, rows=rows)
+    e = rel_err(to_np(out)[:, rows], ref)
+    assert e <= TOL_BF16_OUT, f"{e:.3e}"
+
+
 def test_gate_projection_feeds_the_readout_full_size(lib, oracle):
     """Headline shape: G = sigmoid(x W_g) on the GPU against the oracle, then used as the readout's gate."""
     w = W.WORKLOADS["wan_layer"]

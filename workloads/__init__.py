@@ -141,12 +141,13 @@ def feature_weights(w: Workload, seed: int = 0) -> Tuple[torch.Tensor, torch.Ten
     return tuple(out)
 
 
-def gate_inputs(w: Workload, chunk: int, p: int, seed: int = 0) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Hidden state x [B, L, H*D] ~ N(0,1) and gate weights Wg [H, H*D] ~ N(0, 0.01 / (H*D)) in the stored
-    dtype: logits with standard deviation 0.1, i.e. gates spread over about 0.45..0.55 like the learned ones."""
+def gate_inputs(w: Workload, chunk: int, p: int, seed: int = 0, n_out: int = 0) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Hidden state x [B, L, H*D] ~ N(0,1) and gate weights Wg [n_out, H*D] ~ N(0, 0.01 / (H*D)) in the stored
+    dtype (n_out = H rows unless given: H*D rows make the element-wise gate): logits with standard deviation
+    0.1, i.e. gates spread over about 0.45..0.55 like the learned ones."""
     dm = w.H * w.D
     x = _store(_generator(seed, w.name, chunk, p, _XH).standard_normal((w.B, w.L, dm), dtype=np.float32), w.io_dtype)
-    Wg = _store(_generator(seed, w.name, 0, 0, _WG).standard_normal((w.H, dm)) * (0.1 / np.sqrt(dm)), w.io_dtype)
+    Wg = _store(_generator(seed, w.name, 0, 0, _WG).standard_normal((n_out or w.H, dm)) * (0.1 / np.sqrt(dm)), w.io_dtype)
     return x, Wg
 
 
