@@ -155,23 +155,29 @@ __global__ __launch_bounds__(NTH, 512 / NTH) void gate_dense_kernel(GateArgs a, 
     const int prow = tid >> 3, pcol = tid & 7;           // piece i of this thread: row prow + PR i, 16-byte column pcol
     const int nk = (dm + GK - 1) / GK;
 
+    // byte offsets of this thread's pieces at step 0; rows past the end point past the buffer (reads return zero)
+    uint32_t xoff[XCHD], woff[WCHD];
+#pragma unroll
+    for (int i = 0; i < XCHD; ++i) {
+        const int row = prow + PR * i;
+        xoff[i] = tok0 + row < ntok ? (uint32_t)((tok0 + row) * dm * 2 + 16 * pcol) : x_bytes;
+    }
+#pragma unroll
+    for (int i = 0; i < WCHD; ++i) {
+        const int row = prow + PR * i;
+        woff[i] = n0 + row < N ? (uint32_t)((long long)(n0 + row) * dm * 2 + 16 * pcol) : w_bytes;
+    }
     u32x4 xr[2][XCHD], wr[2][WCHD];
     auto fetch = [&](int kc, auto j_) __attribute__((always_inline)) {   // step kc into register set j; rows and columns past the end read zeros
         constexpr int j = decltype(j_)::value;
-        const int colb = 2 * GK * kc + 16 * pcol;
-        const bool okc = kc < nk && colb < 2 * dm;
+        const uint32_t colb = 2 * GK * kc;
+        const bool okc = kc < nk && (int)colb + 16 * pcol < 2 * dm;
 #pragma unroll
-        for (int i = 0; i < XCHD; ++i) {
-            const int row = prow + PR * i;
-            xr[j][i] = __builtin_amdgcn_raw_buffer_load_b128(
-                x_rsrc, okc && tok0 + row < ntok ? (uint32_t)((tok0 + row) * dm * 2 + colb) : x_bytes, 0, 0);
-        }
+        for (int i = 0; i < XCHD; ++i)
+            xr[j][i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, okc && xoff[i] != x_bytes ? xoff[i] + colb : x_bytes, 0, 0);
 #pragma unroll
-        for (int i = 0; i < WCHD; ++i) {
-            const int row = prow + PR * i;
-            wr[j][i] = __builtin_amdgcn_raw_buffer_load_b128(
-                w_rsrc, okc && n0 + row < N ? (uint32_t)((long long)(n0 + row) * dm * 2 + colb) : w_bytes, 0, 0);
-        }
+        for (int i = 0; i < WCHD; ++i)
+            wr[j][i] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, okc && woff[i] != w_bytes ? woff[i] + colb : w_bytes, 0, 0);
     };
     auto stage = [&](int st, auto j_) __attribute__((always_inline)) {
         constexpr int j = decltype(j_)::value;
@@ -208,20 +214,21 @@ __global__ __launch_bounds__(NTH, 512 / NTH) void gate_dense_kernel(GateArgs a, 
 
     const std::integral_constant<int, 0> J0{};
     const std::integral_constant<int, 1> J1{};
-    // step kc lives in register set kc % 2 and LDS stage kc % 2
+    // Step kc lives in register set kc % 2 and LDS stage kc % 2.  A step requests the loads of step kc + 2
+    // first (its register set was staged in the previous step), contracts stage kc % 2 and then stages step
+    // kc + 1, whose loads were requested a whole step earlier.
     fetch(0, J0);
     fetch(1, J1);
     stage(0, J0);
-    fetch(2, J0);
     lds_barrier();
     for (int kc = 0; kc < nk; kc += 2) {
+        fetch(kc + 2, J0);
         contract(0);
         stage(1, J1);                 // step kc + 1 (zeros past the end); stage 1 was last read before the previous barrier
-        fetch(kc + 3, J1);
         lds_barrier();
+        fetch(kc + 3, J1);
         if (kc + 1 < nk) contract(1);
         stage(0, J0);
-        fetch(kc + 4, J0);
         lds_barrier();
     }
 
