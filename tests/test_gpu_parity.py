@@ -620,6 +620,7 @@ def test_gate_projection_small(lib, oracle, B, L, H, D, gdt):
     (1, 130, 5, 64, 0, "f32"),        # three output tiles, five steps
     (3, 77, 2, 128, 0, "f32"),        # fewer tokens than a tile per stream, tiles across streams
     (1, 150, 40, 64, 40, "f32"),      # headwise with more heads than the skinny kernel takes
+    (2, 90, 33, 64, 33, "bf16"),      # rows of g that are not 16-byte aligned: element-by-element stores
 ])
 def test_gate_projection_dense(lib, oracle, B, L, H, D, n_out, gdt):
     """More than 32 gate outputs per token (the element-wise gate, or very many heads): the dense kernel."""
@@ -635,7 +636,8 @@ def test_gate_projection_dense(lib, oracle, B, L, H, D, n_out, gdt):
     ref = oracle.gate_proj(to_np(x), to_np(Wg)).reshape(g.shape)
     assert ref.min() < 0.3 and ref.max() > 0.7
     err = np.abs(to_np(g) - ref).max()
-    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9), f"{err:.3e}"
+    # fp32 arithmetic: 2e-6; a bf16 gate adds its rounding, half an ulp below 1 = 2^-9
+    assert err <= (2e-6 if gdt == "f32" else 2.0 ** -9 + 2e-6), f"{err:.3e}"
 
 
 @pytest.mark.parametrize("B,L,H,D,gdt", [
