@@ -286,8 +286,10 @@ def test_rollout_step_latency_is_flat(lib):
           f"min/median {ms.min() / med:.3f}, least-squares drift over the rollout {slope * w.chunks / med * 100:+.2f} % of median",
           flush=True)
     print("[wan_rollout] ms per chunk:", " ".join(f"{x:.3f}" for x in ms), flush=True)
-    assert slope * w.chunks < 0.05 * med, "per-chunk latency grows with the chunk index"
-    assert np.percentile(ms, 90) < 1.15 * med
+    # a cost that grew with the history (a cache of past chunks) would show up as hundreds of per cent;
+    # the margins leave room for clock drift on a power-limited launch
+    assert slope * w.chunks < 0.10 * med, "per-chunk latency grows with the chunk index"
+    assert np.percentile(ms, 90) < 1.25 * med
     assert torch.isfinite(S).all()
 
 
