@@ -134,6 +134,16 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Workgroup barrier that waits only until at most N of this wavefront's LDS operations are outstanding:
+// LDS operations complete in order, so everything issued before the last N is done (writes published),
+// while the last N (reads of data that stays valid) remain in flight across the barrier.
+template <int N>
+__device__ __forceinline__ void lds_barrier_keep()
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
 // 1 / sqrt(x) in one hardware instruction (about 1 ulp); x > 0.
 __device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
 

@@ -48,9 +48,8 @@ namespace {
 constexpr int BM = 256;   // query rows per workgroup
 constexpr int BN = 64;    // keys per tile
 constexpr int NT = 512;   // threads per workgroup
-constexpr int NSTAGE = 3; // LDS ring depth
-constexpr int PF = 7;     // operand fragments are read from LDS this many MFMAs ahead
-constexpr int RING = 8;   // fragment registers (PF + 1)
+constexpr int NSTAGE = 4; // LDS ring depth (a power of two)
+constexpr int kStoreStep0 = 4;   // the tile copy's LDS writes go into steps 4, 6, ... of an interval's second slot
 
 template <int D>
 struct FwdCfg {
@@ -79,8 +78,23 @@ struct FwdCfg {
     static constexpr int SMEM = SMEM0 > FM_BYTES ? SMEM0 : FM_BYTES;
     static constexpr int KCH = BN * CPR / NT;    // 16-byte chunks per thread per tile (K and V each)
     static constexpr int ROWS_PER_PASS = NT / CPR;
-    static constexpr int S_LEN = 2 * KS;         // MFMAs of one S^T chain (two 32-key blocks)
-    static constexpr int PV_LEN = 4 * DB;        // MFMAs of one PV chain
+    static constexpr int S_LEN = KS;             // MFMAs of the S^T chain of one 32-key block
+    static constexpr int PV_LEN = 2 * DB;        // MFMAs of the PV chain of one 32-key block
+    static constexpr int RING = S_LEN < 8 ? S_LEN : 8;   // fragment registers in flight from LDS
+#ifndef PFD
+#define PFD (RING - 1)
+#endif
+    static constexpr int PF = PFD < RING ? PFD : RING - 1;          // operand fragments are read from LDS this many MFMAs ahead
+    // LDS reads a full slot issues after step `first` (its own fragments, then the next slot's; S fragments,
+    // at even positions, are one read, V^T fragments two)
+    static constexpr int lds_reads_from(int first)
+    {
+        int c = 0;
+        for (int n = first; n < S_LEN + PV_LEN; ++n) c += ((n + PF) & 1) == 0 ? 1 : 2;
+        return c;
+    }
+    static constexpr int LDS_AFTER_COPY = lds_reads_from(kStoreStep0 + 4 * KCH - 1);
+    static_assert(kStoreStep0 + 4 * KCH - 2 < S_LEN + PV_LEN && 2 * KCH - 1 < S_LEN + PV_LEN, "the copy must fit into one slot");
     static_assert(KCH >= 1, "tile too small for the workgroup");
     static_assert(S_LEN % RING == 0 && PV_LEN % RING == 0, "chain lengths must be multiples of the fragment ring");
 };
@@ -112,8 +126,6 @@ __device__ __forceinline__ void static_for(F &&f)
         static_for<I + 1, N>(f);
     }
 }
-
-enum ChainKind { kNone = 0, kS = 1, kPV = 2 };
 
 template <int D>
 __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2, int ragged_last)
@@ -191,6 +203,20 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         }
         g_off += BN * tok_bytes;
     };
+    // the same copy in pieces: part h of the loads (chunk h of K and of V), piece p of the stores
+    auto load_tile_part = [&](auto h_) {
+        constexpr int h = decltype(h_)::value;
+        const uint32_t off = g_off + (uint32_t)h * C::ROWS_PER_PASS * tok_bytes;
+        kst[h] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, off, 0, 0);
+        vst[h] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, off, 0, 0);
+        if constexpr (h == C::KCH - 1) g_off += BN * tok_bytes;
+    };
+    auto store_tile_part = [&](int stage, auto p_) {
+        constexpr int p = decltype(p_)::value;
+        unsigned char *smK = smem + stage * C::STAGE;
+        if constexpr ((p & 1) == 0) *(u32x4 *)(smK + lds_k_off + (p >> 1) * C::ROWS_PER_PASS * C::KROW) = kst[p >> 1];
+        else *(u32x4 *)(smK + C::K_BYTES + lds_v_off + (p >> 1) * C::ROWS_PER_PASS * C::VROW) = vst[p >> 1];
+    };
     auto store_tile = [&](int stage) {
         unsigned char *smK = smem + stage * C::STAGE;
         unsigned char *smV = smK + C::K_BYTES;
@@ -201,15 +227,15 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
         }
     };
 
-    // lane roles inside a tile
-    const int k_frag_off = c * C::KROW + 16 * hh;                                   // + 32*KROW*kb + 32*t
-    const int v_frag_off = C::K_BYTES + (((lane & 15) >> 2) + 4 * hh) * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    // lane roles inside a 32-key block
+    const int k_frag_off = c * C::KROW + 16 * hh;                                   // + 32*t
+    const int v_frag_off = (((lane & 15) >> 2) + 4 * hh) * C::VROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
 
     // ---- running softmax state and accumulators
     f32x16 o_acc[C::DB];         // O^T blocks
-    f32x16 s_acc[2];             // S^T blocks of the tile in flight
-    bf16x8 pf[4];                // P^T fragments (B operands of the second GEMM)
-    bf16x8 fr[RING];             // A-operand fragments in flight from LDS
+    f32x16 s_acc[2];             // S^T of the key block whose softmax runs, and of the next one
+    bf16x8 pf[4];                // P^T fragments (B operands of the second GEMM): two per key block
+    bf16x8 fr[C::RING];          // A-operand fragments in flight from LDS
     float m_run = -INFINITY;     // running max of scaled logits (log2 domain)
     float l_run = 0.f;           // this lane's share of the running sum
 #pragma unroll
@@ -217,89 +243,143 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
 
-    // A-operand fragment n of a chain: for S^T = K Q^T (k-step n/2 of key block n%2) a K row
-    // piece, for O^T += V^T P^T (16-key step n/DB, row block n%DB) a transposed V piece.
-    auto load_frag = [&](auto kind_, int stage, auto n_) -> bf16x8 {
+    // Byte offsets in the ring of the K rows / V rows of 32-key block `blk` (tile blk / 2, half blk % 2).
+    auto k_block = [&](int blk) -> int { return ((blk >> 1) & (NSTAGE - 1)) * C::STAGE + (blk & 1) * 32 * C::KROW; };
+    auto v_block = [&](int blk) -> int { return ((blk >> 1) & (NSTAGE - 1)) * C::STAGE + C::K_BYTES + (blk & 1) * 32 * C::VROW; };
+    // A-operand fragments: k-step n of S^T = K Q^T (a K row piece), and MFMA n of O^T += V^T P^T
+    // (16-key step n / DB, row block n % DB: a transposed V piece).
+    auto k_frag = [&](const unsigned char *kp, auto n_) -> bf16x8 {
+        return *(const bf16x8 *)(kp + 32 * decltype(n_)::value);
+    };
+    auto v_frag = [&](const unsigned char *vp, auto n_) -> bf16x8 {
         constexpr int n = decltype(n_)::value;
-        if constexpr (decltype(kind_)::value == kS) {
-            return *(const bf16x8 *)(smem + stage * C::STAGE + k_frag_off + 32 * (n & 1) * C::KROW + 32 * (n >> 1));
-        } else {
-            const unsigned char *vp = smem + stage * C::STAGE + v_frag_off + 16 * (n / C::DB) * C::VROW + 64 * (n % C::DB);
-            const bf16x4 lo = lds_read_tr(vp);                    // keys 16t + 4hh + 0..3
-            const bf16x4 hi = lds_read_tr(vp + 8 * C::VROW);      // keys 16t + 8 + 4hh + 0..3
-            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
+        const unsigned char *p = vp + 16 * (n / C::DB) * C::VROW + 64 * (n % C::DB);
+        const bf16x4 lo = lds_read_tr(p);                    // keys 16u + 4hh + 0..3
+        const bf16x4 hi = lds_read_tr(p + 8 * C::VROW);      // keys 16u + 8 + 4hh + 0..3
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    // Requests the first PF fragments of a chain (they must be in flight when the chain starts).
-    auto prefetch_chain = [&](auto kind_, int stage) {
-        static_for<0, PF>([&](auto m_) { fr[decltype(m_)::value] = load_frag(kind_, stage, m_); });
-    };
-    // Runs one MFMA chain; every step also requests the fragment needed PF MFMAs later, which at the
-    // end of the chain is a fragment of the chain that runs next (kind kNone: nothing follows).
-    auto run_chain = [&](auto kind_, int stage, auto next_kind_, int next_stage) {
-        constexpr int KIND = decltype(kind_)::value, NEXT = decltype(next_kind_)::value;
-        constexpr int LEN = KIND == kS ? C::S_LEN : C::PV_LEN;
-        static_for<0, LEN>([&](auto n_) {
-            constexpr int n = decltype(n_)::value;
-            constexpr int m = n + PF;
-            if constexpr (m < LEN) fr[m % RING] = load_frag(kind_, stage, std::integral_constant<int, m>{});
-            else if constexpr (NEXT != kNone) fr[m % RING] = load_frag(next_kind_, next_stage, std::integral_constant<int, m - LEN>{});
-            if constexpr (KIND == kS) {
-                constexpr int t = n >> 1, kb = n & 1;
-                if constexpr (t == 0) {
-                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], zero, 0, 0, 0);
-                } else {
-                    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[t], s_acc[kb], 0, 0, 0);
-                }
-            } else {
-                constexpr int t = n / C::DB, db = n % C::DB;
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], pf[t], o_acc[db], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-    // exp2 of all 32 logits per lane relative to the running maximum -> P^T fragments in pf;
-    // returns this lane's share of the row sum.  Accumulator registers 8*(t&1)..+7 of key block
-    // t/2 are one B operand (fragment t) of the second GEMM.
-    auto exp_all = [&]() -> float {
+    // exp2 of the 16 logits per lane of one key block relative to the running maximum -> its two P^T
+    // fragments; returns this lane's share of the row sum.  (Only on the rare path that raises the maximum.)
+    auto exp_block = [&](auto par_) -> float {
+        constexpr int PAR = decltype(par_)::value;
         const float mneg = -m_run;
         float psum = 0.f;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int j = 0; j < 8; j += 2) {
-                const int r = 8 * (t & 1) + j;
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r], scale_log2, mneg));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[t >> 1][r + 1], scale_log2, mneg));
-                psum += p0 + p1;
-                pf[t][j] = to_bf16(p0);
-                pf[t][j + 1] = to_bf16(p1);
-            }
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[PAR][r], scale_log2, mneg));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[PAR][r + 1], scale_log2, mneg));
+            psum += p0 + p1;
+            pf[2 * PAR + (r >> 3)][r & 7] = to_bf16(p0);
+            pf[2 * PAR + (r >> 3)][(r & 7) + 1] = to_bf16(p1);
+        }
         return psum;
     };
-    // Online softmax of the tile in s_acc.  The probabilities are first taken relative to the running
-    // maximum as it stands; only if some lane's share of the row sum shows that a logit exceeded it by
-    // more than the threshold (or the maximum is still -inf: first tile) is the true tile maximum
-    // computed, the running maximum raised, the accumulators rescaled and the tile redone.
-    auto softmax = [&](int kv0, auto masked_) {
-        constexpr bool masked = decltype(masked_)::value;
-        if constexpr (masked) {          // keys past the end of the sequence (last tile only)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kvl = 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (kv0 + kvl >= Lkv) s_acc[kb][r] = -INFINITY;
+
+    // One slot of the software pipeline, on key block j (logits in s_acc[j % 2], produced one slot earlier):
+    //   matrix pipe:  S(j+1) = K_{j+1} Q^T  -> s_acc[(j+1) % 2]     (KS MFMAs, if the block exists)
+    //                 O^T += V_{j-1}^T P_{j-1}^T                      (2 DB MFMAs, if j > 0)
+    //   vector ALU:   softmax of block j -> its P^T fragments and row-sum share
+    // Neither MFMA chain depends on this slot's vector work, so every step issues one MFMA, the LDS read of
+    // the operand fragment needed PF MFMAs later (at the end of the slot: of the next slot's first chain)
+    // and a slice of the softmax; the slices are themselves staggered (scale of logit v+2, exponential of
+    // logit v+1, sum and conversion of logit v) so that no instruction waits for the one before it.
+    // copy_: 0 nothing; 1 this slot also requests the next K/V tile from global memory (early steps);
+    // 2 it also writes that tile, by now in registers, into ring stage `cstage`, one 16-byte piece per thread
+    // every other step, so that the copy runs under the MFMAs instead of in a burst before the barrier.
+    auto slot = [&](auto par_, auto has_s_, auto has_pv_, auto next_s_, auto masked_, int j, auto copy_, int cstage) {
+        constexpr int PAR = decltype(par_)::value;
+        constexpr int COPY = decltype(copy_)::value;
+        constexpr bool HAS_S = decltype(has_s_)::value, HAS_PV = decltype(has_pv_)::value;
+        constexpr bool NEXT_S = decltype(next_s_)::value, MASKED = decltype(masked_)::value;
+        constexpr int SL = HAS_S ? C::S_LEN : 0, NS = SL + (HAS_PV ? C::PV_LEN : 0);
+        constexpr int LPS = 16 / NS;                 // logits per step
+        static_assert(NS % C::RING == 0 && 16 % NS == 0, "slot length");
+        const unsigned char *kp = smem + k_block(j + 1) + k_frag_off;
+        const unsigned char *vp = smem + v_block(j - 1) + v_frag_off;
+        const unsigned char *np = smem + k_block(j + 2) + k_frag_off;      // next slot: S(j+2) (if any) and PV(j)
+        const unsigned char *nvp = smem + v_block(j) + v_frag_off;
+        const float mneg = -m_run;
+        float x[16], ps0 = 0.f, ps1 = 0.f;
+        auto op_scale = [&](auto v_) {               // logit v: scaled, relative to the running maximum
+            constexpr int v = decltype(v_)::value;
+            if constexpr (v < 16) {
+                if constexpr (MASKED) {              // keys past the end of the sequence (last tile only)
+                    const int kvl = 8 * (v >> 2) + 4 * hh + (v & 3);
+                    if (32 * j + kvl >= Lkv) s_acc[PAR][v] = -INFINITY;
                 }
-        }
-        float psum = exp_all();
-        if (__any(!(psum < kRowSumLimit))) {      // wave-uniform and rare; also true for inf and NaN
-            float mx = s_acc[0][0];
+                x[v] = fmaf(s_acc[PAR][v], scale_log2, mneg);
+            }
+        };
+        auto op_exp = [&](auto v_) {
+            constexpr int v = decltype(v_)::value;
+            if constexpr (v < 16) x[v] = __builtin_amdgcn_exp2f(x[v]);
+        };
+        auto op_sum = [&](auto v_) {                 // row-sum share, and the P^T pair (v-1, v) for odd v
+            constexpr int v = decltype(v_)::value;
+            if constexpr (v & 1) {
+                ps1 += x[v];
+                bf16x2 pk = {to_bf16(x[v - 1]), to_bf16(x[v])};
+                asm volatile("" : "+v"(pk));         // the conversion stays in this step
+                pf[2 * PAR + (v >> 3)][(v & 7) - 1] = pk[0];
+                pf[2 * PAR + (v >> 3)][v & 7] = pk[1];
+            } else {
+                ps0 += x[v];
+            }
+        };
+        // MFMA n of the slot: with both chains present they alternate (S at even n), so that MFMAs which
+        // accumulate into the same registers are never issued back to back
+        auto is_s = [](int n) constexpr { return HAS_S && (!HAS_PV || (n & 1) == 0); };
+        auto idx = [](int n) constexpr { return HAS_S && HAS_PV ? n >> 1 : n; };
+        auto fetch = [&](auto m_) {                  // requests the A fragment of MFMA m (m >= NS: of the next slot)
+            constexpr int m = decltype(m_)::value;
+            if constexpr (m < NS) {
+                if constexpr (is_s(m)) fr[m % C::RING] = k_frag(kp, std::integral_constant<int, idx(m)>{});
+                else fr[m % C::RING] = v_frag(vp, std::integral_constant<int, idx(m)>{});
+            } else {
+                // the next slot has a second GEMM (this slot's block) in every case; its S chain alternates with it
+                constexpr int mm = m - NS;
+                if constexpr (NEXT_S && (mm & 1) == 0) fr[m % C::RING] = k_frag(np, std::integral_constant<int, (mm >> 1)>{});
+                else fr[m % C::RING] = v_frag(nvp, std::integral_constant<int, (NEXT_S ? mm >> 1 : mm)>{});
+            }
+        };
+        static_for<0, NS>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+            fetch(std::integral_constant<int, n + C::PF>{});
+            if constexpr (is_s(n)) {
+                constexpr int t = idx(n);
+                if constexpr (t == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    s_acc[PAR ^ 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], qf[t], zero, 0, 0, 0);
+                } else {
+                    s_acc[PAR ^ 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], qf[t], s_acc[PAR ^ 1], 0, 0, 0);
+                }
+            } else {
+                constexpr int u = idx(n) / C::DB, db = idx(n) % C::DB;
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], pf[2 * (PAR ^ 1) + u], o_acc[db], 0, 0, 0);
+            }
+            if constexpr (COPY == 1 && (n & 1) == 1 && n / 2 < C::KCH) load_tile_part(std::integral_constant<int, n / 2>{});
+            if constexpr (COPY == 2 && n >= kStoreStep0 && n < kStoreStep0 + 4 * C::KCH && ((n - kStoreStep0) & 1) == 0)
+                store_tile_part(cstage, std::integral_constant<int, (n - kStoreStep0) / 2>{});
+            if constexpr (n == 0) {
+                op_scale(std::integral_constant<int, 0>{});
+                op_scale(std::integral_constant<int, 1>{});
+                op_exp(std::integral_constant<int, 0>{});
+            }
+            static_for<0, LPS>([&](auto i_) {
+                constexpr int v = n * LPS + decltype(i_)::value;
+                op_scale(std::integral_constant<int, v + 2>{});
+                op_exp(std::integral_constant<int, v + 1>{});
+                op_sum(std::integral_constant<int, v>{});
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        float psum = ps0 + ps1;
+        // Rarely (always on the first block) a logit exceeded the running maximum by more than the
+        // threshold: take the true block maximum, raise the running maximum, rescale, redo the block.
+        if (__any(!(psum < kRowSumLimit))) {      // wave-uniform; also true for inf and NaN
+            float mx = s_acc[PAR][0];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_acc[PAR][r]);
             mx = xhalf_max(mx) * scale_log2;
             const float m_new = fmaxf(m_run, mx);
             const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
@@ -309,14 +389,19 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
             for (int db = 0; db < C::DB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
-            psum = exp_all();
+            psum = exp_block(par_);
         }
         l_run += psum;
     };
 
     const int ntiles = (Lkv + BN - 1) / BN;
-    const std::false_type unmasked{};
-    const std::true_type masked{};
+    const std::false_type no{};
+    const std::true_type yes{};
+    const std::integral_constant<int, 0> par0{};
+    const std::integral_constant<int, 1> par1{};
+    const std::integral_constant<int, 0> copy0{};
+    const std::integral_constant<int, 1> copy1{};
+    const std::integral_constant<int, 2> copy2{};
 
     // ---- prologue: tiles 0 and 1 into the ring
     load_tile();
@@ -325,44 +410,78 @@ __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles
     store_tile(1);
     __syncthreads();
 
-    // Barrier interval i (tile i in ring stage i % 3): tile i+2 is fetched into registers at its
-    // start and written to the stage of tile i-1 at its end (free since the barrier that opened
-    // the interval); the barrier that closes it publishes tile i+2 and retires tile i.
-    int st_cur = 0, st_next = 1, st_free = 2;
-    auto close_interval = [&]() {
-        store_tile(st_free);
+    // Barrier interval i covers the slots of key blocks 2i and 2i+1: they read K of tiles i and i+1 and V of
+    // tiles i-1 and i.  Tile i+2 is fetched into registers at its start and written at its end to the ring
+    // stage of tile i-2 (four stages); the barrier that closes the interval publishes it.
+    auto close_interval = [&](int i) {
+        store_tile((i + 2) & (NSTAGE - 1));
         __syncthreads();
-        const int tmp = st_cur; st_cur = st_next; st_next = st_free; st_free = tmp;
     };
 
-    const std::integral_constant<int, kS> S_{};
-    const std::integral_constant<int, kPV> PV_{};
-    const std::integral_constant<int, kNone> NONE_{};
     if (q0 < Lq) {
-        prefetch_chain(S_, st_cur);
-#pragma unroll 1
-        for (int it = 0; it < ntiles - 1; ++it) {
-            load_tile();
-            run_chain(S_, st_cur, PV_, st_cur);
-            softmax(0, unmasked);
-            run_chain(PV_, st_cur, S_, st_next);
-            close_interval();
+        // S(0), plain: nothing to overlap it with
+        {
+            const unsigned char *kp = smem + k_block(0) + k_frag_off;
+            const unsigned char *np = smem + k_block(1) + k_frag_off;
+            static_for<0, C::PF>([&](auto m_) { fr[decltype(m_)::value] = k_frag(kp, m_); });
+            static_for<0, C::S_LEN>([&](auto n_) {
+                constexpr int n = decltype(n_)::value;
+                constexpr int m = n + C::PF;
+                if constexpr (m < C::S_LEN) fr[m % C::RING] = k_frag(kp, std::integral_constant<int, m>{});
+                else fr[m % C::RING] = k_frag(np, std::integral_constant<int, m - C::S_LEN>{});
+                if constexpr (n == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    s_acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], qf[n], zero, 0, 0, 0);
+                } else {
+                    s_acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], qf[n], s_acc[0], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
         load_tile();
-        run_chain(S_, st_cur, PV_, st_cur);
-        softmax((ntiles - 1) * BN, masked);
-        run_chain(PV_, st_cur, NONE_, 0);
-        __syncthreads();
+        if (ntiles == 1) {
+            slot(par0, yes, no, no, yes, 0, copy0, 0);
+            slot(par1, no, yes, no, yes, 1, copy0, 0);
+        } else {
+            slot(par0, yes, no, yes, no, 0, copy0, 0);
+            slot(par1, yes, yes, yes, no, 1, copy0, 0);
+        }
+        close_interval(0);
+#pragma unroll 1
+        for (int i = 1; i < ntiles - 1; ++i) {
+            slot(par0, yes, yes, yes, no, 2 * i, copy1, 0);
+            slot(par1, yes, yes, yes, no, 2 * i + 1, copy2, (i + 2) & (NSTAGE - 1));
+            // the writes are complete once at most the LDS reads issued after the last of them are still
+            // outstanding (LDS operations complete in order); those reads stay in flight across the barrier
+            lds_barrier_keep<C::LDS_AFTER_COPY>();
+        }
+        if (ntiles > 1) {
+            const int i = ntiles - 1;
+            slot(par0, yes, yes, no, yes, 2 * i, copy0, 0);
+            slot(par1, no, yes, no, yes, 2 * i + 1, copy0, 0);
+        }
+        // second GEMM of the last key block (its first fragments are in flight)
+        {
+            const unsigned char *vp = smem + v_block(2 * ntiles - 1) + v_frag_off;
+            static_for<0, C::PV_LEN>([&](auto n_) {
+                constexpr int n = decltype(n_)::value;
+                constexpr int m = n + C::PF;
+                if constexpr (m < C::PV_LEN) fr[m % C::RING] = v_frag(vp, std::integral_constant<int, m>{});
+                o_acc[n % C::DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % C::RING], pf[2 + n / C::DB], o_acc[n % C::DB], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
     } else {
         // A wavefront whose 32 rows all lie past the last query (the ragged last workgroup of a head) only
         // helps to move the tiles: the same loads, stores and barriers, no arithmetic.  Its rows are never
         // stored.
+        load_tile();
+        close_interval(0);
 #pragma unroll 1
-        for (int it = 0; it < ntiles - 1; ++it) {
+        for (int i = 1; i < ntiles - 1; ++i) {
             load_tile();
-            close_interval();
+            close_interval(i);
         }
-        __syncthreads();
         l_run = 1.0f;
     }
 
