@@ -80,11 +80,8 @@ struct FwdCfg {
     static constexpr int ROWS_PER_PASS = NT / CPR;
     static constexpr int S_LEN = KS;             // MFMAs of the S^T chain of one 32-key block
     static constexpr int PV_LEN = 2 * DB;        // MFMAs of the PV chain of one 32-key block
-    static constexpr int RING = S_LEN < 8 ? S_LEN : 8;   // fragment registers in flight from LDS
-#ifndef PFD
-#define PFD (RING - 1)
-#endif
-    static constexpr int PF = PFD < RING ? PFD : RING - 1;          // operand fragments are read from LDS this many MFMAs ahead
+    static constexpr int RING = 4;               // fragment registers in flight from LDS
+    static constexpr int PF = RING - 1;          // operand fragments are read from LDS this many MFMAs ahead
     // LDS reads a full slot issues after step `first` (its own fragments, then the next slot's; S fragments,
     // at even positions, are one read, V^T fragments two)
     static constexpr int lds_reads_from(int first)
