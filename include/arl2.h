@@ -179,6 +179,23 @@ arl2_status arl2_state_commit(const arl2_desc *desc,
                               const float *gate, float *S);
 
 /*
+ * arl2_state_commit for callers that can neither allocate device memory nor bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; desc->workspace and desc->workspace_bytes are ignored, the token-split
+ * partial sums go to a fixed array in device memory that the library holds on every GPU it runs on
+ * (arl2_static_scratch_bytes(), 16 MiB).  A problem that needs more returns ARL2_ERR_UNSUPPORTED
+ * (bf16: B * H * splits * D * D * 4 bytes, 12 MiB at B = 1, H = 12, Lq = 4680, D = 128; fp32: B * Lq * H * 4
+ * bytes).  The call allocates and frees nothing and does not synchronise.  All calls on one GPU share that
+ * GPU's array: two calls that overlap in time on one GPU (different streams, or threads) race; calls on
+ * one stream, or ordered by events, do not.  Nothing in the array has to survive between calls or to be
+ * cleared: every call writes each partial sum before it reads it.
+ */
+size_t arl2_static_scratch_bytes(void);
+arl2_status arl2_state_commit_static(const arl2_desc *desc,
+                                     const void *k, const void *v,
+                                     const float *gate, float *S);
+
+/*
  * Post-denoise state update with the delta-correction term: paper Eq. (4) taken literally at
  * frame level,
  *     S <- alpha * S + beta * K'^T (V - K' S),      K' = L2Norm(k) per token (Eq. (3)),

@@ -20,6 +20,7 @@ ARL2_F32, ARL2_BF16 = 0, 1
 ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT, ARL2_GATE_PER_TOKEN = 0, 1, 2
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
+           "arl2_static_scratch_bytes", "arl2_state_commit_static",
            "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_hybrid_attn_fwd_fm", "arl2_feature_map", "arl2_gate_proj",
            "arl2_status_string", "arl2_last_error", "arl2_version"]
 
@@ -57,6 +58,10 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_hybrid_attn_fwd.restype = ctypes.c_int
         lib.arl2_state_commit.argtypes = [dp, vp, vp, vp, vp]
         lib.arl2_state_commit.restype = ctypes.c_int
+        lib.arl2_state_commit_static.argtypes = [dp, vp, vp, vp, vp]
+        lib.arl2_state_commit_static.restype = ctypes.c_int
+        lib.arl2_static_scratch_bytes.argtypes = []
+        lib.arl2_static_scratch_bytes.restype = ctypes.c_size_t
         lib.arl2_state_commit_delta.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_state_commit_delta.restype = ctypes.c_int
         lib.arl2_hybrid_attn_fwd_ex.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
@@ -257,6 +262,23 @@ def arl2_state_commit(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor, S: t
     B, L, H, D = k.shape
     d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, workspace=workspace, stream=stream)
     st = load_library().arl2_state_commit(
+        ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
+        _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
+    _check(st)
+
+
+def arl2_static_scratch_bytes() -> int:
+    return int(load_library().arl2_static_scratch_bytes())
+
+
+def arl2_state_commit_static(k: torch.Tensor, v: torch.Tensor, gate: torch.Tensor, S: torch.Tensor, *,
+                             l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """``arl2_state_commit`` without a workspace: the partial sums go to the library's fixed device array."""
+    if k.dim() != 4:
+        raise ValueError("k must be [B, L, H, D]")
+    B, L, H, D = k.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, stream=stream)
+    st = load_library().arl2_state_commit_static(
         ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
         _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
     _check(st)

@@ -3,6 +3,7 @@
 #include "../../include/arl2.h"
 #include "arl2_device.h"
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -50,6 +51,14 @@ size_t commit_workspace(const arl2_desc *d)
 {
     if (d->io_dtype == ARL2_BF16)   // two partial matrices per split (delta rule) plus one state snapshot
         return (size_t)d->B * d->H * (2 * arl2::commit_nsplit(d->B, d->H, d->Lq) + 1) * d->D * d->D * sizeof(float);
+    return (size_t)d->B * d->Lq * d->H * sizeof(float);
+}
+
+// What the plain commit alone needs (no delta-rule matrices, no state snapshot).
+size_t commit_workspace_plain(const arl2_desc *d)
+{
+    if (d->io_dtype == ARL2_BF16)
+        return (size_t)d->B * d->H * arl2::commit_nsplit(d->B, d->H, d->Lq) * d->D * d->D * sizeof(float);
     return (size_t)d->B * d->Lq * d->H * sizeof(float);
 }
 
@@ -209,7 +218,7 @@ static arl2_status commit_common(const arl2_desc *desc, const void *k, const voi
         return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_delta takes bf16 k, v only");
     if (desc->io_dtype == ARL2_BF16 && !fits_32bit(((double)desc->Lq + 256.0) * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
-    const size_t need = commit_workspace(desc);
+    const size_t need = delta ? commit_workspace(desc) : commit_workspace_plain(desc);
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
     if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
@@ -271,6 +280,56 @@ arl2_status arl2_state_commit_gdn(const arl2_desc *desc, const void *k, const vo
     const hipError_t e = arl2::launch_commit_gdn_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
     if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "gdn commit launch failed: %s", hipGetErrorString(e));
     return ARL2_OK;
+}
+
+// ---- entry point that allocates nothing ---------------------------------------------------------------
+// The commit's token-split partial sums go to a fixed device array instead of a caller's workspace.  Every
+// GPU the library runs on holds its own copy of the array (at its own address) until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, looked up once
+
+// The array's name is a host-side stand-in, not a device address: the address on the current device comes
+// from the runtime, once per device, and only that pointer is ever handed to a kernel.
+arl2_status static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ARL2_ERR_UNSUPPORTED, "device ordinal beyond the static scratch table");
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(ARL2_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread would look up the same address
+    }
+    *out = p;
+    return ARL2_OK;
+}
+
+}  // namespace
+
+size_t arl2_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+arl2_status arl2_state_commit_static(const arl2_desc *desc, const void *k, const void *v, const float *gate, float *S)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    const size_t need = commit_workspace_plain(desc);
+    if (need > kStaticScratchBytes)
+        return fail(ARL2_ERR_UNSUPPORTED, "problem needs more scratch than the static array holds (arl2_static_scratch_bytes)");
+    void *ptr = nullptr;
+    st = static_scratch(&ptr);
+    if (st != ARL2_OK) return st;
+    arl2_desc d = *desc;
+    d.workspace = ptr;
+    d.workspace_bytes = kStaticScratchBytes;
+    return commit_common(&d, k, v, gate, nullptr, false, S);
 }
 
 const char *arl2_status_string(arl2_status s)
