@@ -31,8 +31,11 @@
  *
  * All data pointers are DEVICE pointers owned by the caller, 16-byte aligned and
  * contiguous in the layouts below.  The library never allocates, frees or
- * synchronises: every call validates its arguments on the host, enqueues its kernels
- * on desc->stream and returns.  A call that returns an error has launched nothing.
+ * synchronises: every call validates its arguments on the host (sizes, alignment, overlapping
+ * buffers, limits of the kernels), enqueues its kernels on desc->stream and returns.  A call that
+ * returns ARL2_ERR_INVALID_ARG, ARL2_ERR_UNSUPPORTED or ARL2_ERR_WORKSPACE has launched nothing.
+ * ARL2_ERR_DEVICE reports that the runtime refused a launch: a call made of several kernels
+ * (the state commits) may then have enqueued the earlier ones, and S is undefined.
  * The kernels address one stream's k, v (the whole x for arl2_feature_map and arl2_gate_proj) with
  * 32-bit byte offsets: such an array must stay below 2 GiB, larger problems return ARL2_ERR_UNSUPPORTED.
  *
@@ -234,7 +237,8 @@ arl2_status arl2_state_commit_gdn(const arl2_desc *desc,
 
 const char *arl2_status_string(arl2_status s);
 
-/* Thread-local detail of the last failing call on this thread ("" if none). */
+/* Thread-local detail of the last call that failed on this thread ("" if none has failed yet); a later
+ * successful call does not clear it: read it right after a call that returned an error. */
 const char *arl2_last_error(void);
 
 /* Library version, major * 10000 + minor * 100 + patch. */

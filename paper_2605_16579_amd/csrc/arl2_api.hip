@@ -19,6 +19,29 @@ arl2_status fail(arl2_status s, const char *fmt, const char *detail = "")
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Do the byte ranges [a, a + na) and [b, b + nb) share a byte?  (NULL pointers overlap nothing.)
+bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (a == nullptr || b == nullptr || na == 0 || nb == 0) return false;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+size_t elem_bytes(int dtype) { return dtype == ARL2_BF16 ? 2 : 4; }
+size_t q_bytes(const arl2_desc *d) { return (size_t)d->B * d->Lq * d->H * d->D * elem_bytes(d->io_dtype); }
+size_t kv_bytes(const arl2_desc *d) { return (size_t)d->B * d->Lkv * d->H * d->D * elem_bytes(d->io_dtype); }
+size_t state_bytes(const arl2_desc *d) { return (size_t)d->B * d->H * d->D * d->D * sizeof(float); }
+size_t g_bytes(const arl2_desc *d)
+{
+    const size_t per_token = d->g_mode == ARL2_GATE_PER_TOKEN ? 1 : d->g_mode == ARL2_GATE_PER_ELEMENT ? (size_t)d->H * d->D : (size_t)d->H;
+    return (size_t)d->B * d->Lq * per_token * elem_bytes(d->g_dtype);
+}
+size_t table_bytes(const arl2_desc *d) { return (size_t)d->Lq * (d->D / 2) * sizeof(float); }
+size_t wmap_bytes(const arl2_desc *d) { return (size_t)d->H * d->D * d->D * 2; }
+
+// The fp32 kernels put heads and streams on the grid's y and z axes.
+bool f32_grid_ok(const arl2_desc *d) { return d->io_dtype != ARL2_F32 || (d->H <= 65535 && d->B <= 65535); }
+
 // Checks everything that does not depend on which call is made.
 arl2_status check_desc(const arl2_desc *d)
 {
@@ -84,12 +107,17 @@ arl2_status arl2_hybrid_attn_fwd_ex(const arl2_desc *desc, const void *q, const 
         return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
     if (g && desc->g_mode == ARL2_GATE_PER_ELEMENT && !aligned16(g))
         return fail(ARL2_ERR_INVALID_ARG, "an element-wise g must be 16-byte aligned");
-    if (out == q || out == k || out == v || out == q_lin)
-        return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
     if (S != nullptr && desc->Lkv != desc->Lq)
         return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
+    if (!f32_grid_ok(desc)) return fail(ARL2_ERR_UNSUPPORTED, "fp32 inputs: H and B must stay below 65536");
     if (desc->io_dtype == ARL2_BF16 && !fits_32bit(((double)desc->Lkv + 256.0) * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
+    {
+        const size_t nq = q_bytes(desc), nkv = kv_bytes(desc);
+        if (overlaps(out, nq, q, nq) || overlaps(out, nq, k, nkv) || overlaps(out, nq, v, nkv) || overlaps(out, nq, q_lin, nq) ||
+            overlaps(out, nq, S, state_bytes(desc)) || overlaps(out, nq, g, g_bytes(desc)))
+            return fail(ARL2_ERR_INVALID_ARG, "out must not overlap an input");
+    }
 
     arl2::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.S = S; a.g = (S != nullptr) ? g : nullptr; a.out = out;
@@ -131,12 +159,17 @@ arl2_status arl2_hybrid_attn_fwd_fm(const arl2_desc *desc, const void *q, const 
     if (g && (reinterpret_cast<uintptr_t>(g) & 3u)) return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
     if (g && desc->g_mode == ARL2_GATE_PER_ELEMENT && !aligned16(g))
         return fail(ARL2_ERR_INVALID_ARG, "an element-wise g must be 16-byte aligned");
-    if (out == q || out == k || out == v || out == xq || out == Wq)
-        return fail(ARL2_ERR_INVALID_ARG, "out must not alias an input");
     if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq when a state is given");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_hybrid_attn_fwd_fm takes bf16 inputs only");
     if (!fits_32bit(((double)desc->Lkv + 256.0) * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "one stream's k (or v) must stay below 2 GiB");
+    {
+        const size_t nq = q_bytes(desc), nkv = kv_bytes(desc);
+        if (overlaps(out, nq, q, nq) || overlaps(out, nq, k, nkv) || overlaps(out, nq, v, nkv) || overlaps(out, nq, xq, nq) ||
+            overlaps(out, nq, Wq, wmap_bytes(desc)) || overlaps(out, nq, S, state_bytes(desc)) || overlaps(out, nq, g, g_bytes(desc)) ||
+            overlaps(out, nq, rope_cos, table_bytes(desc)) || overlaps(out, nq, rope_sin, table_bytes(desc)))
+            return fail(ARL2_ERR_INVALID_ARG, "out must not overlap an input");
+    }
 
     arl2::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.S = S; a.g = g; a.out = out; a.q_lin = nullptr;
@@ -164,10 +197,15 @@ arl2_status arl2_feature_map(const arl2_desc *desc, const void *x, const void *W
         return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
     if ((reinterpret_cast<uintptr_t>(rope_cos) & 7u) || (reinterpret_cast<uintptr_t>(rope_sin) & 7u))
         return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be 8-byte aligned");
-    if (y == x || y == W) return fail(ARL2_ERR_INVALID_ARG, "y must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_feature_map takes bf16 x, W only");
     if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
+    {
+        const size_t nx = q_bytes(desc);
+        if (overlaps(y, nx, x, nx) || overlaps(y, nx, W, wmap_bytes(desc)) || overlaps(y, nx, rope_cos, table_bytes(desc)) ||
+            overlaps(y, nx, rope_sin, table_bytes(desc)))
+            return fail(ARL2_ERR_INVALID_ARG, "y must not overlap an input");
+    }
 
     arl2::FmapArgs a;
     a.x = x; a.W = W; a.cs = rope_cos; a.sn = rope_sin; a.y = y;
@@ -184,13 +222,18 @@ arl2_status arl2_gate_proj(const arl2_desc *desc, const void *x, const void *Wg,
     if (!x || !Wg || !g) return fail(ARL2_ERR_INVALID_ARG, "x, Wg and g must not be NULL");
     if (!aligned16(x) || !aligned16(Wg)) return fail(ARL2_ERR_INVALID_ARG, "x and Wg must be 16-byte aligned");
     if (reinterpret_cast<uintptr_t>(g) & 3u) return fail(ARL2_ERR_INVALID_ARG, "g must be 4-byte aligned");
-    if (g == x || g == Wg) return fail(ARL2_ERR_INVALID_ARG, "g must not alias an input");
     if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_gate_proj takes bf16 x, Wg only");
     if (!fits_32bit((double)desc->B * desc->Lq * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "x must stay below 2 GiB");
     const int n_out = desc->g_mode == ARL2_GATE_PER_TOKEN ? 1 : desc->g_mode == ARL2_GATE_PER_ELEMENT ? desc->H * desc->D : desc->H;
     if (!fits_32bit((double)n_out * desc->H * desc->D, 2))
         return fail(ARL2_ERR_UNSUPPORTED, "Wg must stay below 2 GiB");
+    {
+        const size_t nx = (size_t)desc->B * desc->Lq * desc->H * desc->D * 2;
+        const size_t rows = desc->g_mode == ARL2_GATE_PER_TOKEN ? 1 : desc->g_mode == ARL2_GATE_PER_ELEMENT ? (size_t)desc->H * desc->D : (size_t)desc->H;
+        if (overlaps(g, g_bytes(desc), x, nx) || overlaps(g, g_bytes(desc), Wg, rows * desc->H * desc->D * 2))
+            return fail(ARL2_ERR_INVALID_ARG, "g must not overlap an input");
+    }
 
     arl2::GateArgs a;
     a.x = x; a.Wg = Wg; a.g = g;
@@ -222,6 +265,16 @@ static arl2_status commit_common(const arl2_desc *desc, const void *k, const voi
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
     if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    if (!f32_grid_ok(desc)) return fail(ARL2_ERR_UNSUPPORTED, "fp32 inputs: H and B must stay below 65536");
+    {
+        const size_t ns = state_bytes(desc), nkv = kv_bytes(desc), ngate = (size_t)desc->B * desc->H * sizeof(float);
+        if (overlaps(S, ns, k, nkv) || overlaps(S, ns, v, nkv) || overlaps(S, ns, gate, ngate) || overlaps(S, ns, beta, ngate) ||
+            overlaps(S, ns, desc->workspace, need))
+            return fail(ARL2_ERR_INVALID_ARG, "S must not overlap k, v, the gates or the workspace");
+        if (overlaps(desc->workspace, need, k, nkv) || overlaps(desc->workspace, need, v, nkv) ||
+            overlaps(desc->workspace, need, gate, ngate) || overlaps(desc->workspace, need, beta, ngate))
+            return fail(ARL2_ERR_INVALID_ARG, "the workspace must not overlap an input");
+    }
 
     arl2::CommitArgs a;
     a.k = k; a.v = v; a.gate = gate; a.beta = delta ? beta : nullptr; a.S = S; a.workspace = desc->workspace;
@@ -272,6 +325,15 @@ arl2_status arl2_state_commit_gdn(const arl2_desc *desc, const void *k, const vo
     if (desc->workspace == nullptr || desc->workspace_bytes < need)
         return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_gdn_workspace_bytes()");
     if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    {
+        const size_t ns = state_bytes(desc), nkv = kv_bytes(desc), ngate = (size_t)desc->B * desc->Lq * desc->H * sizeof(float);
+        if (overlaps(S, ns, k, nkv) || overlaps(S, ns, v, nkv) || overlaps(S, ns, alpha, ngate) || overlaps(S, ns, beta, ngate) ||
+            overlaps(S, ns, desc->workspace, need))
+            return fail(ARL2_ERR_INVALID_ARG, "S must not overlap k, v, the gates or the workspace");
+        if (overlaps(desc->workspace, need, k, nkv) || overlaps(desc->workspace, need, v, nkv) ||
+            overlaps(desc->workspace, need, alpha, ngate) || overlaps(desc->workspace, need, beta, ngate))
+            return fail(ARL2_ERR_INVALID_ARG, "the workspace must not overlap an input");
+    }
 
     arl2::GdnArgs a;
     a.k = k; a.v = v; a.alpha = alpha; a.beta = beta; a.S = S; a.workspace = desc->workspace;

@@ -33,28 +33,6 @@ constexpr int BT = 64;    // tokens per tile
 constexpr int NT = 512;    // partial kernel: 8 wavefronts, two per SIMD
 constexpr int NTR = 256;   // reduce kernels
 
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
-__device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char *p, int second_row_bytes)
-{
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p + second_row_bytes));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 constexpr int PFT = 3;     // tiles whose loads are in flight (register ring): HBM latency is several tile times
 constexpr int PFW = 3;     // the same for the producer wavefronts of the plain commit, which hold no accumulators
@@ -500,31 +478,27 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
     // the kernel addresses one stream's K (or V) with 32-bit byte offsets
     if ((long long)(a.L + 4 * BT) * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool delta = a.beta != nullptr;
+    hipError_t e;
     if (a.D == 128 && !delta)
-        hipLaunchKernelGGL(commit_partial_ws_kernel<128>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        e = launch_kernel(commit_partial_ws_kernel<128>, dim3((unsigned)nwg), dim3(NT), stream, a);
     else if (a.D == 64 && !delta)
-        hipLaunchKernelGGL(commit_partial_ws_kernel<64>, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        e = launch_kernel(commit_partial_ws_kernel<64>, dim3((unsigned)nwg), dim3(NT), stream, a);
     else if (a.D == 128)
-        hipLaunchKernelGGL((commit_partial_kernel<128, true>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        e = launch_kernel(commit_partial_kernel<128, true>, dim3((unsigned)nwg), dim3(NT), stream, a);
     else if (a.D == 64)
-        hipLaunchKernelGGL((commit_partial_kernel<64, true>), dim3((unsigned)nwg), dim3(NT), 0, stream, a);
+        e = launch_kernel(commit_partial_kernel<64, true>, dim3((unsigned)nwg), dim3(NT), stream, a);
     else
         return hipErrorInvalidValue;
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (delta) {
         const int rows = NTR / (a.D / 4);
         const long long rwg = (long long)a.B * a.H * (a.D / rows);
-        if (a.D == 128)
-            hipLaunchKernelGGL(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a);
-        else
-            hipLaunchKernelGGL(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a);
-        return hipGetLastError();
+        if (a.D == 128) return launch_kernel(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NTR), stream, a);
+        return launch_kernel(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NTR), stream, a);
     }
     const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
     const long long rwg = (long long)a.B * a.H * (vec_per_head / NTR);
-    hipLaunchKernelGGL(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NTR), 0, stream, a, vec_per_head);
-    return hipGetLastError();
+    return launch_kernel(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NTR), stream, a, vec_per_head);
 }
 
 }  // namespace arl2

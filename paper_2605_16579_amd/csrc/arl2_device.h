@@ -6,6 +6,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 namespace arl2 {
 
 typedef __bf16 bf16_t;
@@ -23,6 +27,12 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kNumXcd = 8;
 constexpr int kNumCu = 256;
 constexpr int kWave = 64;
+
+template <class Tuple, size_t... I>
+inline void fill_arg_pointers(void **ptrs, Tuple &vals, std::index_sequence<I...>)
+{
+    ((ptrs[I] = (void *)&std::get<I>(vals)), ...);
+}
 
 struct FwdArgs {
     const void *q, *k, *v;
@@ -95,7 +105,48 @@ hipError_t launch_gate_proj_bf16(const GateArgs &a, hipStream_t stream);
 // Workspace of the token-sequential commit (per-block transition maps).
 size_t gdn_workspace_bytes(int B, int H, int L, int D);
 
+// ---- launching ------------------------------------------------------------------------
+// Enqueues `kernel` and returns the status of this launch alone (an error that an earlier, unrelated HIP call
+// of the caller left behind is neither reported nor cleared).
+template <class... Params, class... Args>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args)
+{
+    std::tuple<Params...> vals{static_cast<Params>(args)...};
+    void *ptrs[sizeof...(Params) > 0 ? sizeof...(Params) : 1];
+    fill_arg_pointers(ptrs, vals, std::index_sequence_for<Params...>{});
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, stream);
+}
+
 // ---- small device helpers -------------------------------------------------------------
+
+// Raw buffer descriptor over [base, base + bytes): loads beyond the range return zero, stores are dropped.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = First .. N - 1.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16): within each group of 16 lanes, lane i receives element i of the
+// four 16-element rows whose 8-byte pieces are addressed by lanes 4j..4j+3 (j = 0..3).
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
+}
+// Two such reads, `second_row_bytes` apart, as one 8-element MFMA operand fragment.
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char *p, int second_row_bytes)
+{
+    return __builtin_shufflevector(lds_read_tr(p), lds_read_tr(p + second_row_bytes), 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // Sum / max of a value held by lane l and lane l^32 (the two half-waves).
 __device__ __forceinline__ float xhalf_sum(float x)

@@ -148,24 +148,18 @@ hipError_t launch_fwd_f32(const FwdArgs &a, hipStream_t stream)
 {
     const dim3 grid((a.Lq + ROWS - 1) / ROWS, a.H, a.B), block(NT);
     if (a.H > 65535 || a.B > 65535) return hipErrorInvalidValue;
-    if (a.D == 64)
-        hipLaunchKernelGGL(fwd_f32_kernel<64>, grid, block, 0, stream, a);
-    else if (a.D == 128)
-        hipLaunchKernelGGL(fwd_f32_kernel<128>, grid, block, 0, stream, a);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (a.D == 64) return launch_kernel(fwd_f32_kernel<64>, grid, block, stream, a);
+    if (a.D == 128) return launch_kernel(fwd_f32_kernel<128>, grid, block, stream, a);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream)
 {
     if (a.H > 65535 || a.B > 65535) return hipErrorInvalidValue;
     const size_t n = (size_t)a.B * a.L * a.H;
-    hipLaunchKernelGGL(knorm_f32_kernel, dim3((unsigned)((n + NT - 1) / NT)), dim3(NT), 0, stream, a);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch_kernel(knorm_f32_kernel, dim3((unsigned)((n + NT - 1) / NT)), dim3(NT), stream, a);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(commit_f32_kernel, dim3(a.D, a.H, a.B), dim3(a.D), 0, stream, a);
-    return hipGetLastError();
+    return launch_kernel(commit_f32_kernel, dim3(a.D, a.H, a.B), dim3(a.D), stream, a);
 }
 
 }  // namespace arl2

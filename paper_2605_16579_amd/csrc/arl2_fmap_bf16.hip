@@ -28,20 +28,6 @@ constexpr int HG = 4;      // heads per workgroup
 constexpr int TT = 32;     // tokens per tile
 constexpr int MAX_NTILE = 16;  // most tiles per workgroup (W stays in registers across them)
 
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
 // PIPE: the x rows of the next tile are requested while the current one is computed (for workgroups that
 // walk several tiles; with a single tile the extra live registers only cost: 8 spill at D = 128).
 template <int D, bool PIPE>
@@ -227,17 +213,11 @@ hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream)
     // x and y are addressed with 32-bit byte offsets
     if ((long long)a.B * a.L * a.H * a.D * 2 > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nwg), block(NT);
-    if (a.D == 128 && ntile > 1)
-        hipLaunchKernelGGL((feature_map_kernel<128, true>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
-    else if (a.D == 128)
-        hipLaunchKernelGGL((feature_map_kernel<128, false>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
-    else if (a.D == 64 && ntile > 1)
-        hipLaunchKernelGGL((feature_map_kernel<64, true>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
-    else if (a.D == 64)
-        hipLaunchKernelGGL((feature_map_kernel<64, false>), grid, block, 0, stream, a, n_ranges, n_hg, (int)ntile);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (a.D == 128 && ntile > 1) return launch_kernel(feature_map_kernel<128, true>, grid, block, stream, a, n_ranges, n_hg, (int)ntile);
+    if (a.D == 128) return launch_kernel(feature_map_kernel<128, false>, grid, block, stream, a, n_ranges, n_hg, (int)ntile);
+    if (a.D == 64 && ntile > 1) return launch_kernel(feature_map_kernel<64, true>, grid, block, stream, a, n_ranges, n_hg, (int)ntile);
+    if (a.D == 64) return launch_kernel(feature_map_kernel<64, false>, grid, block, stream, a, n_ranges, n_hg, (int)ntile);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace arl2

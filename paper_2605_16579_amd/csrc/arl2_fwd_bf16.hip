@@ -100,29 +100,6 @@ struct FwdCfg {
 // relative to the running maximum) reaches this value, i.e. some logit exceeded it by more than ~2^7.
 constexpr float kRowSumLimit = 4096.0f;
 
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
-// Transposing LDS read: within each group of 16 lanes, lane i receives element i of the four
-// 16-element rows whose 8-byte pieces are addressed by lanes 4j..4j+3 (j = 0..3).
-__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p)
-{
-    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
-}
-
-// Raw buffer descriptor over [base, base + bytes): loads beyond the range return zero.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 template <int D>
 __global__ __launch_bounds__(NT, 2) void fwd_bf16_kernel(FwdArgs a, int n_qtiles, float scale_log2, int ragged_last)
@@ -715,13 +692,9 @@ hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)nwg), block(NT);
     // more workgroups than CUs, a ragged last query tile per head, and whole heads per XCD
     const int ragged_last = nwg > kNumCu && a.Lq % BM != 0 && n_qtiles > 1 && ((long long)a.B * a.H) % kNumXcd == 0;
-    if (a.D == 128)
-        hipLaunchKernelGGL(fwd_bf16_kernel<128>, grid, block, 0, stream, a, n_qtiles, scale_log2, ragged_last);
-    else if (a.D == 64)
-        hipLaunchKernelGGL(fwd_bf16_kernel<64>, grid, block, 0, stream, a, n_qtiles, scale_log2, ragged_last);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (a.D == 128) return launch_kernel(fwd_bf16_kernel<128>, grid, block, stream, a, n_qtiles, scale_log2, ragged_last);
+    if (a.D == 64) return launch_kernel(fwd_bf16_kernel<64>, grid, block, stream, a, n_qtiles, scale_log2, ragged_last);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace arl2

@@ -24,11 +24,6 @@ constexpr int CW = 512;                  // columns of x per chunk
 constexpr int XROW = 2 * CW + 16;        // LDS bytes per token row of a chunk (conflict-free 16-byte reads)
 constexpr int XCH = 32 * (2 * CW / 16) / NT;   // 16-byte pieces of a chunk per thread
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
 __global__ __launch_bounds__(NT) void gate_proj_kernel(GateArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char xs[2][32 * XROW];
@@ -279,8 +274,7 @@ hipError_t launch_gate_dense(const GateArgs &a, long long ntok, hipStream_t stre
 {
     const long long n_ntile = (a.n_out + TN - 1) / TN, n_mtile = (ntok + TM - 1) / TM;
     if (n_mtile * n_ntile > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gate_dense_kernel<TM, TN, NTH>), dim3((unsigned)(n_mtile * n_ntile)), dim3(NTH), 0, stream, a, (int)n_ntile);
-    return hipGetLastError();
+    return launch_kernel(gate_dense_kernel<TM, TN, NTH>, dim3((unsigned)(n_mtile * n_ntile)), dim3(NTH), stream, a, (int)n_ntile);
 }
 
 }  // namespace
@@ -298,8 +292,7 @@ hipError_t launch_gate_proj_bf16(const GateArgs &a, hipStream_t stream)
         const long long big = ((ntok + 255) / 256) * ((a.n_out + 255) / 256);
         return big >= 2 * kNumCu ? launch_gate_dense<256, 256, 512>(a, ntok, stream) : launch_gate_dense<128, 128, 256>(a, ntok, stream);
     }
-    hipLaunchKernelGGL(gate_proj_kernel, dim3((unsigned)nwg), dim3(NT), 0, stream, a);
-    return hipGetLastError();
+    return launch_kernel(gate_proj_kernel, dim3((unsigned)nwg), dim3(NT), stream, a);
 }
 
 }  // namespace arl2

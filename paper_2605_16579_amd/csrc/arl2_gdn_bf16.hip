@@ -36,28 +36,6 @@ constexpr int NTA = 256;   // threads of the block kernel
 constexpr int GDN_PFD = 2;    // blocks whose operands the scan keeps in flight
 constexpr int GDN_EARLY = 2;  // k-steps of the next operands that the scan requests before its MFMAs start
 
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
-__device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char *p, int second_row_bytes)
-{
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p + second_row_bytes));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
 template <int D>
 struct GdnCfg {
@@ -762,26 +740,22 @@ static hipError_t launch_gdn(const GdnArgs &a, int nblk, unsigned nwg, hipStream
     const int groups = gdn_groups(a.B, a.H, nblk, D);
     const unsigned char *recs = (const unsigned char *)a.workspace;
     unsigned char *gmaps = (unsigned char *)a.workspace + (size_t)heads * nblk * gdn_ops_bytes(D);
-    hipLaunchKernelGGL(gdn_block_kernel<D>, dim3(nwg), dim3(NTA), 0, stream, a, nblk);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_kernel(gdn_block_kernel<D>, dim3(nwg), dim3(NTA), stream, a, nblk);
     if (e != hipSuccess) return e;
     // whole owners per XCD: ceil(owners / 8) on each of the 8 XCDs
     const unsigned owners8 = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd);
     if (groups == 1) {
-        hipLaunchKernelGGL((gdn_walk_kernel<D, false>), dim3(owners8 * NSL), dim3(256), 0, stream, a, recs, nblk, 1,
-                           (unsigned char *)nullptr);
-        return hipGetLastError();
+        return launch_kernel(gdn_walk_kernel<D, false>, dim3(owners8 * NSL), dim3(256), stream, a, recs, nblk, 1,
+                             (unsigned char *)nullptr);
     }
     // the runs after the first (c and M slices), then the first runs (c slices)
     const unsigned late8 = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd);
-    hipLaunchKernelGGL((gdn_walk_kernel<D, true>), dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), 0, stream, a, recs, nblk,
-                       groups, gmaps);
-    e = hipGetLastError();
+    e = launch_kernel(gdn_walk_kernel<D, true>, dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), stream, a, recs, nblk,
+                      groups, gmaps);
     if (e != hipSuccess) return e;
     // the composite maps of the later runs, applied in order to what the first run left in S
-    hipLaunchKernelGGL(gdn_apply_kernel<D>, dim3(owners8 * (D / 32)), dim3(2 * D), 0, stream, a, (const unsigned char *)gmaps,
-                       groups - 1);
-    return hipGetLastError();
+    return launch_kernel(gdn_apply_kernel<D>, dim3(owners8 * (D / 32)), dim3(2 * D), stream, a, (const unsigned char *)gmaps,
+                         groups - 1);
 }
 
 hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream)

@@ -53,7 +53,7 @@ def test_workspace_bytes(A):
     assert A.load_library().arl2_workspace_bytes(ctypes.byref(d)) == 0
 
 
-def _fwd(A, d, q=0x1000, k=0x2000, v=0x3000, S=0x4000, g=0x5000, out=0x6000):
+def _fwd(A, d, q=0x10000000, k=0x20000000, v=0x30000000, S=0x40000000, g=0x50000000, out=0x60000000):
     # the pointers are never dereferenced: every call below must fail validation before any launch
     return A.load_library().arl2_hybrid_attn_fwd(ctypes.byref(d), q, k, v, S, g, out)
 
@@ -69,8 +69,11 @@ def test_fwd_rejects_bad_arguments_before_launch(A):
     d = A.make_desc(**ok, stream=0)
     assert _fwd(A, d, q=None) == 1
     assert _fwd(A, d, out=None) == 1
-    assert _fwd(A, d, q=0x1004) == 1                      # misaligned
-    assert _fwd(A, d, out=0x1000) == 1                    # out aliases q
+    assert _fwd(A, d, q=0x10000004) == 1                      # misaligned
+    assert _fwd(A, d, out=0x10000000) == 1                    # out aliases q
+    assert _fwd(A, d, out=0x10000100) == 1 and b"overlap" in lib.arl2_last_error()   # out = q + one row: overlaps, not equal
+    assert _fwd(A, d, out=0x40000040) == 1                    # out inside the state
+    assert _fwd(A, d, out=0x20000000 - 256) == 1              # out ends inside k
     d2 = A.make_desc(**{**ok, "Lkv": 128}, stream=0)
     assert _fwd(A, d2) == 1                               # Lkv != Lq with a state
     assert b"Lkv" in lib.arl2_last_error()
@@ -81,25 +84,25 @@ def test_fwd_rejects_bad_arguments_before_launch(A):
 def test_commit_rejects_bad_arguments_before_launch(A):
     lib = A.load_library()
     d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
-    call = lambda d, k=0x1000, v=0x2000, gate=0x3000, S=0x4000: lib.arl2_state_commit(ctypes.byref(d), k, v, gate, S)
+    call = lambda d, k=0x10000000, v=0x20000000, gate=0x30000000, S=0x40000000: lib.arl2_state_commit(ctypes.byref(d), k, v, gate, S)
     assert call(d) == 3                                   # no workspace
-    d.workspace, d.workspace_bytes = 0x10000, 16
+    d.workspace, d.workspace_bytes = 0x70000000, 16
     assert call(d) == 3                                   # too small
     d.workspace_bytes = A.arl2_workspace_bytes(1, 2, 64, 64, A.ARL2_BF16)
     assert call(d, S=None) == 1
-    assert call(d, gate=0x3002) == 1
+    assert call(d, gate=0x30000002) == 1
     d.Lkv = 32
     assert call(d) == 1
     # delta-rule variant: needs beta, and bf16 inputs
     d.Lkv = 64
-    delta = lambda d, beta=0x5000: lib.arl2_state_commit_delta(ctypes.byref(d), 0x1000, 0x2000, 0x3000, beta, 0x4000)
+    delta = lambda d, beta=0x50000000: lib.arl2_state_commit_delta(ctypes.byref(d), 0x10000000, 0x20000000, 0x30000000, beta, 0x40000000)
     assert delta(d, beta=None) == 1
-    assert delta(d, beta=0x5002) == 1
+    assert delta(d, beta=0x50000002) == 1
     df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
-    df.workspace, df.workspace_bytes = 0x10000, 1 << 20
+    df.workspace, df.workspace_bytes = 0x70000000, 1 << 20
     assert delta(df) == 2
     # token-sequential variant: its own workspace size, per-token gates, bf16 inputs
-    gdn = lambda d, alpha=0x3000, beta=0x5000: lib.arl2_state_commit_gdn(ctypes.byref(d), 0x1000, 0x2000, alpha, beta, 0x4000)
+    gdn = lambda d, alpha=0x30000000, beta=0x50000000: lib.arl2_state_commit_gdn(ctypes.byref(d), 0x10000000, 0x20000000, alpha, beta, 0x40000000)
     need = A.arl2_gdn_workspace_bytes(1, 2, 64, 64)
     assert need == 2 * (64 * 64 * 8 + 1024)               # two heads, one block of 64 tokens each: Z^T hi/lo, K, V^T, scalars
     assert A.arl2_gdn_workspace_bytes(1, 2, 65, 64) == 2 * need
@@ -107,7 +110,7 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     assert gdn(d) == 3                                    # one byte short
     d.workspace_bytes = need
     assert gdn(d, alpha=None) == 1
-    assert gdn(d, beta=0x5002) == 1
+    assert gdn(d, beta=0x50000002) == 1
     df.workspace_bytes = 1 << 24
     assert gdn(df) == 2
 
@@ -115,32 +118,32 @@ def test_commit_rejects_bad_arguments_before_launch(A):
 def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
     lib = A.load_library()
     d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
-    fm = lambda d, x=0x1000, W=0x2000, c=0x3000, s=0x4000, y=0x5000: lib.arl2_feature_map(ctypes.byref(d), x, W, c, s, y)
+    fm = lambda d, x=0x10000000, W=0x20000000, c=0x30000000, s=0x40000000, y=0x50000000: lib.arl2_feature_map(ctypes.byref(d), x, W, c, s, y)
     assert fm(d, W=None) == 1
     assert fm(d, c=None) == 1                             # cosines without sines
-    assert fm(d, c=0x3004) == 1                           # tables must be 8-byte aligned
-    assert fm(d, y=0x1000) == 1                           # in place
+    assert fm(d, c=0x30000004) == 1                           # tables must be 8-byte aligned
+    assert fm(d, y=0x10000000) == 1                           # in place
     df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
     assert fm(df) == 2
     dg = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
     dg.g_mode = 7
-    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x1000, 0x2000, 0x3000, 0x4000, 0x7000, 0x5000) == 1   # not a gate mode
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x74000000, 0x50000000) == 1   # not a gate mode
     dg.g_mode = A.ARL2_GATE_PER_ELEMENT
-    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x1000, 0x2000, 0x3000, 0x4000, 0x7004, 0x5000) == 1   # element-wise g: 16-byte aligned
-    ex = lambda d, ql=0x6000, out=0x5000: lib.arl2_hybrid_attn_fwd_ex(ctypes.byref(d), 0x1000, 0x2000, 0x3000, ql, 0x4000, None, out)
-    assert ex(d, ql=0x6008) == 1                          # misaligned q_lin
-    assert ex(d, ql=0x5000) == 1                          # out aliases q_lin
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(dg), 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x74000004, 0x50000000) == 1   # element-wise g: 16-byte aligned
+    ex = lambda d, ql=0x60000000, out=0x50000000: lib.arl2_hybrid_attn_fwd_ex(ctypes.byref(d), 0x10000000, 0x20000000, 0x30000000, ql, 0x40000000, None, out)
+    assert ex(d, ql=0x60000008) == 1                          # misaligned q_lin
+    assert ex(d, ql=0x50000000) == 1                          # out aliases q_lin
 
 
 def test_fused_feature_map_readout_rejects_bad_arguments(A):
     lib = A.load_library()
     d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
-    fm = lambda d, xq=0x6000, W=0x7000, c=0x8000, s=0x9000, S=0x4000, out=0x5000: lib.arl2_hybrid_attn_fwd_fm(
-        ctypes.byref(d), 0x1000, 0x2000, 0x3000, xq, W, c, s, S, None, out)
+    fm = lambda d, xq=0x60000000, W=0x74000000, c=0x78000000, s=0x7c000000, S=0x40000000, out=0x50000000: lib.arl2_hybrid_attn_fwd_fm(
+        ctypes.byref(d), 0x10000000, 0x20000000, 0x30000000, xq, W, c, s, S, None, out)
     assert fm(d, S=None) == 1                             # no state, no linear branch
     assert fm(d, xq=None) == 1
     assert fm(d, s=None) == 1                             # cosines without sines
-    assert fm(d, out=0x6000) == 1                         # out aliases xq
+    assert fm(d, out=0x60000000) == 1                         # out aliases xq
     assert fm(A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)) == 2
     assert fm(A.make_desc(1, 2, 64, 32, 64, A.ARL2_BF16, stream=0)) == 1
 
@@ -148,10 +151,10 @@ def test_fused_feature_map_readout_rejects_bad_arguments(A):
 def test_gate_proj_rejects_bad_arguments(A):
     lib = A.load_library()
     d = A.make_desc(1, 12, 64, 64, 128, A.ARL2_BF16, stream=0)
-    gp = lambda d, x=0x1000, W=0x2000, g=0x3000: lib.arl2_gate_proj(ctypes.byref(d), x, W, g)
+    gp = lambda d, x=0x10000000, W=0x20000000, g=0x30000000: lib.arl2_gate_proj(ctypes.byref(d), x, W, g)
     assert gp(d, x=None) == 1
-    assert gp(d, W=0x2008) == 1
-    assert gp(d, g=0x1000) == 1
+    assert gp(d, W=0x20000008) == 1
+    assert gp(d, g=0x10000000) == 1
     assert gp(A.make_desc(1, 12, 64, 64, 128, A.ARL2_F32, stream=0)) == 2
 
 
@@ -160,20 +163,20 @@ def test_sizes_beyond_the_kernels_addressing_are_refused(A):
     32-bit byte offsets: larger problems return ARL2_ERR_UNSUPPORTED instead of launching."""
     lib = A.load_library()
     big = A.make_desc(1, 64, 200000, 200000, 128, A.ARL2_BF16, stream=0)     # 3.3 GB per stream
-    big.workspace, big.workspace_bytes = 0x10000, 1 << 62
-    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(big), 0x1000, 0x2000, 0x3000, None, None, 0x5000) == 2
-    assert lib.arl2_state_commit(ctypes.byref(big), 0x1000, 0x2000, 0x3000, 0x4000) == 2
-    assert lib.arl2_state_commit_gdn(ctypes.byref(big), 0x1000, 0x2000, 0x3000, 0x6000, 0x4000) == 2
-    assert lib.arl2_feature_map(ctypes.byref(big), 0x1000, 0x2000, None, None, 0x5000) == 2
+    big.workspace, big.workspace_bytes = 0x70000000, 1 << 62
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(big), 0x10000000, 0x20000000, 0x30000000, None, None, 0x50000000) == 2
+    assert lib.arl2_state_commit(ctypes.byref(big), 0x10000000, 0x20000000, 0x30000000, 0x40000000) == 2
+    assert lib.arl2_state_commit_gdn(ctypes.byref(big), 0x10000000, 0x20000000, 0x30000000, 0x60000000, 0x40000000) == 2
+    assert lib.arl2_feature_map(ctypes.byref(big), 0x10000000, 0x20000000, None, None, 0x50000000) == 2
     many = A.make_desc(64, 12, 32768, 32768, 128, A.ARL2_BF16, stream=0)     # each stream small, x as a whole 6.4 GB
-    assert lib.arl2_feature_map(ctypes.byref(many), 0x1000, 0x2000, None, None, 0x5000) == 2
-    assert lib.arl2_gate_proj(ctypes.byref(many), 0x1000, 0x2000, 0x3000) == 2
+    assert lib.arl2_feature_map(ctypes.byref(many), 0x10000000, 0x20000000, None, None, 0x50000000) == 2
+    assert lib.arl2_gate_proj(ctypes.byref(many), 0x10000000, 0x20000000, 0x30000000) == 2
     de = A.make_desc(1, 256, 64, 64, 128, A.ARL2_BF16, stream=0)             # element-wise gate: Wg is 32768 x 32768, 2 GiB
     de.g_mode = A.ARL2_GATE_PER_ELEMENT
-    assert lib.arl2_gate_proj(ctypes.byref(de), 0x1000, 0x2000, 0x3000) == 2
+    assert lib.arl2_gate_proj(ctypes.byref(de), 0x10000000, 0x20000000, 0x30000000) == 2
     assert b"Wg" in lib.arl2_last_error()
     empty = A.make_desc(1, 2, 0, 0, 64, A.ARL2_BF16, stream=0)               # no tokens
-    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(empty), 0x1000, 0x2000, 0x3000, None, None, 0x5000) == 1
+    assert lib.arl2_hybrid_attn_fwd(ctypes.byref(empty), 0x10000000, 0x20000000, 0x30000000, None, None, 0x50000000) == 1
 
 
 def test_binding_refuses_host_tensors(A):
@@ -181,3 +184,21 @@ def test_binding_refuses_host_tensors(A):
     q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         A.arl2_hybrid_attn_fwd(q, q, q, None, None, torch.empty_like(q))
+
+
+def test_overlapping_buffers_are_refused(A):
+    """Buffers that share bytes without being equal pointers are caught by extent, not by pointer equality."""
+    lib = A.load_library()
+    d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    d.workspace, d.workspace_bytes = 0x70000000, A.arl2_workspace_bytes(1, 2, 64, 64, A.ARL2_BF16)
+    k, v, gate, S = 0x10000000, 0x20000000, 0x30000000, 0x40000000
+    assert lib.arl2_state_commit(ctypes.byref(d), k, v, gate, 0x70000100) == 1        # S inside the workspace
+    assert b"overlap" in lib.arl2_last_error()
+    assert lib.arl2_state_commit(ctypes.byref(d), k, v, gate, k + 1024) == 1          # S inside k
+    assert lib.arl2_state_commit(ctypes.byref(d), k, 0x70000000 + 4096, gate, S) == 1   # v inside the workspace
+    assert lib.arl2_state_commit_delta(ctypes.byref(d), k, v, gate, S + 16, S) == 1   # beta inside S
+    d.workspace_bytes = A.arl2_gdn_workspace_bytes(1, 2, 64, 64)
+    assert lib.arl2_state_commit_gdn(ctypes.byref(d), k, v, gate, 0x50000000, v + 256) == 1   # S inside v
+    assert lib.arl2_feature_map(ctypes.byref(d), k, v, None, None, k + 4096) == 1     # y inside x
+    assert lib.arl2_gate_proj(ctypes.byref(d), k, v, k + 64) == 1                      # g inside x
+    assert lib.arl2_hybrid_attn_fwd_ex(ctypes.byref(d), k, v, gate, 0x50000000, S, None, 0x50000000 + 2048) == 1   # out inside q_lin
