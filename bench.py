@@ -80,7 +80,8 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
     Every layer pass is one arl2_hybrid_attn_fwd call at the Wan-2.1-1.3B layer shape: hybrid layers
     read the fixed-size state; softmax layers attend to a KV cache that holds c chunks at chunk c
     (S = NULL, Lkv = c * 4680).  Layer passes of one kind and one cache length cost the same, so each
-    distinct call is timed once (median of `reps`) and the stack total is the weighted sum; inputs are
+    distinct call is timed on its own (median of `reps` batches of back-to-back calls) and the stack total is the
+    weighted sum: a cross-check of the executed rollout (stack_execute), which is the measurement.  Inputs are
     synthetic and there is no model between the layers."""
     w = W.WORKLOADS["wan_layer"]
     P = w.passes
@@ -93,17 +94,19 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
     kv_k = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 101).to(dev)
     kv_v = W.normal(1, w, (w.B, chunks * w.L, w.H, w.D), 102).to(dev)
 
-    def timed(fn):
-        for _ in range(3):
+    def timed(fn, batch=32):
+        """Milliseconds per call: `batch` back-to-back calls between two events (as the calls run in a stack), median of `reps`."""
+        for _ in range(batch):
             fn()
         ts = []
         for _ in range(reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            fn()
+            for _ in range(batch):
+                fn()
             e1.record()
             torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1))
+            ts.append(e0.elapsed_time(e1) / batch)
         return sorted(ts)[len(ts) // 2]
 
     t_hybrid = timed(lambda: A.arl2_hybrid_attn_fwd(q, k, v, S, g, out))
@@ -130,12 +133,119 @@ def stack_report(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, reps=5
     }
 
 
+def stack_execute(A, W, torch, dev, layers=30, hybrid_layers=22, chunks=7, pool=3):
+    """The same stack, executed: for each of `chunks` chunks the chunk's keys and values are appended to the
+    KV cache of every softmax layer, then `passes` readout passes run through all layers in order (a hybrid
+    layer reads its own fixed-size state, a softmax layer attends to its cache, current chunk included), then
+    every hybrid layer commits the chunk.  Both stacks (22 hybrid + 8 softmax-KV, and 30 softmax-KV) run the
+    whole rollout back to back on one stream between two events; peak device memory is what torch's allocator
+    reports for the caches, states and workspace of the stack (inputs and outputs are allocated before the
+    measurement starts and excluded).  Inputs are synthetic: a pool of `pool` pre-drawn (q, k, v, g) sets is
+    cycled over layer passes, there is no model between the layers."""
+    w = W.WORKLOADS["wan_layer"]
+    P, L = w.passes, w.L
+    sets = [tuple(t.to(dev) for t in W.pass_inputs(w, 100 + i, 0)) for i in range(pool)]
+    cleans = [tuple(t.to(dev) for t in W.clean_inputs(w, 100 + i)) for i in range(pool)]
+    out = torch.empty_like(sets[0][0])
+    torch.cuda.synchronize()
+
+    def run(n_hybrid):
+        n_soft = layers - n_hybrid
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        caches = [(torch.empty((w.B, chunks * L, w.H, w.D), dtype=torch.bfloat16, device=dev),
+                   torch.empty((w.B, chunks * L, w.H, w.D), dtype=torch.bfloat16, device=dev)) for _ in range(n_soft)]
+        states = [torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev) for _ in range(n_hybrid)]
+        ws = A.alloc_workspace(w.B, w.H, L, w.D, torch.bfloat16, device=dev) if n_hybrid else None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        calls = 0
+        e0.record()
+        for c in range(chunks):
+            kc, vc, gate = cleans[c % pool]
+            for (ck, cv) in caches:                                  # cache growth: this chunk's K, V appended
+                ck[:, c * L:(c + 1) * L].copy_(kc)
+                cv[:, c * L:(c + 1) * L].copy_(vc)
+            for p in range(P):
+                for l in range(layers):
+                    q, k, v, g = sets[(c + p + l) % pool]
+                    if l < n_hybrid:
+                        A.arl2_hybrid_attn_fwd(q, k, v, states[l], g, out)
+                    else:
+                        ck, cv = caches[l - n_hybrid]
+                        A.arl2_hybrid_attn_fwd(q, ck[:, :(c + 1) * L], cv[:, :(c + 1) * L], None, None, out)
+                    calls += 1
+            for l in range(n_hybrid):
+                A.arl2_state_commit(kc, vc, gate, states[l], ws)
+        e1.record()
+        torch.cuda.synchronize()
+        peak = torch.cuda.max_memory_allocated() - base
+        ms = e0.elapsed_time(e1)
+        del caches, states, ws
+        return ms, peak, calls
+
+    run(hybrid_layers)                                               # warm-up of both code paths and the allocator
+    h_ms, h_mem, h_calls = run(hybrid_layers)
+    s_ms, s_mem, s_calls = run(0)
+    return {"hybrid_stack": {"attention_ms": h_ms, "peak_memory_bytes": h_mem, "readout_calls": h_calls},
+            "softmax_stack": {"attention_ms": s_ms, "peak_memory_bytes": s_mem, "readout_calls": s_calls},
+            "speedup": s_ms / h_ms, "memory_ratio": h_mem / s_mem}
+
+
+def rollout_series(A, W, torch, dev, w, pool=4):
+    """`w.chunks` consecutive chunk steps (passes readouts + 1 commit each) with the state carried from chunk
+    to chunk, every step timed on its own with two events; a pool of `pool` pre-drawn input sets is cycled,
+    every chunk has its own forget gate.  Returns the per-chunk latency series and its flatness figures."""
+    sets = [[tuple(t.to(dev) for t in W.pass_inputs(w, i, p)) for p in range(w.passes)] for i in range(pool)]
+    cleans = [tuple(t.to(dev) for t in W.clean_inputs(w, i)) for i in range(pool)]
+    gates = [W.uniform(0, w, (w.B, w.H), w.gate_lo, w.gate_hi, c, 0, W._GATE).to(dev) for c in range(w.chunks)]
+    outs = [torch.empty_like(sets[0][p][0]) for p in range(w.passes)]
+    S = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device=dev)
+    ws = A.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16, device=dev)
+
+    def rollout(timed):
+        S.zero_()
+        ev = []
+        for c in range(w.chunks):
+            if timed:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            for p in range(w.passes):
+                q, k, v, g = sets[c % pool][p]
+                A.arl2_hybrid_attn_fwd(q, k, v, S, g, outs[p])
+            kc, vc, _ = cleans[c % pool]
+            A.arl2_state_commit(kc, vc, gates[c], S, ws)
+            if timed:
+                e1 = torch.cuda.Event(enable_timing=True)
+                e1.record()
+                ev.append((e0, e1))
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in ev]
+
+    rollout(False)                                                   # warm-up: clocks and caches settle
+    ms = rollout(True)
+    n = len(ms)
+    med = sorted(ms)[n // 2]
+    xm, ym = (n - 1) / 2.0, sum(ms) / n
+    slope = sum((i - xm) * (y - ym) for i, y in enumerate(ms)) / sum((i - xm) ** 2 for i in range(n))
+    return {"chunks": n, "ms_per_chunk": [round(x, 4) for x in ms], "median_ms": med, "max_over_median": max(ms) / med,
+            "p90_over_median": sorted(ms)[int(0.9 * n)] / med, "drift_over_rollout": slope * n / med}
+
+
+def source_sha16(path):
+    import hashlib
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small"])
+    ap.add_argument("--workload", default="wan_layer", choices=["wan_layer", "wan_batched", "ragged_small", "wan_rollout"],
+                    help="wan_layer is the bench workload; wan_rollout runs its 64 chunk steps one after the other, "
+                         "state carried, and reports the per-chunk latency series instead of the bench line")
     ap.add_argument("--commit-rule", default="plain", choices=["plain", "delta", "gdn"],
                     help="state update of the step: plain (the headline: gate * S + K'^T V), delta (Eq. (4) at frame "
                          "level, one learning rate per head), gdn (Eq. (4) token by token, per-token gates)")
@@ -159,6 +269,9 @@ def main() -> int:
     ap.add_argument("--stack-report", action="store_true",
                     help="instead of the bench line: attention time and memory of a 30-layer stack over a "
                          "21-latent-frame rollout (7 chunks), 22 hybrid + 8 softmax-KV layers vs 30 softmax-KV layers")
+    ap.add_argument("--execute", action="store_true",
+                    help="with --stack-report: also run the whole rollout of both stacks for real (KV caches allocated and "
+                         "appended to per chunk, every layer pass launched), time it end to end and report peak memory")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (5 times): the reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -191,7 +304,23 @@ def main() -> int:
     w = W.WORKLOADS[args.workload]
     io_bytes = 2 if w.io_dtype == "bf16" else 4
     if args.stack_report:
-        print(json.dumps(stack_report(A, W, torch, dev)), flush=True)
+        rep = stack_report(A, W, torch, dev)
+        if args.execute:
+            ex = stack_execute(A, W, torch, dev)
+            rep["executed"] = ex
+            rep["executed_over_weighted_sum"] = {
+                "hybrid_stack": ex["hybrid_stack"]["attention_ms"] / rep["hybrid_stack"]["attention_ms"],
+                "softmax_stack": ex["softmax_stack"]["attention_ms"] / rep["softmax_stack"]["attention_ms"]}
+        print(json.dumps(rep), flush=True)
+        return 0
+    if args.workload == "wan_rollout":
+        ser = rollout_series(A, W, torch, dev, w)
+        total_ms = sum(ser["ms_per_chunk"])
+        print(json.dumps({"metric": "per-chunk latency over a 64-chunk rollout (4 readout passes + 1 commit per chunk, state carried)",
+                          "value": w.B * w.L * ser["chunks"] / (total_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+                          "higher_is_better": True, "dtype": w.io_dtype, "data": "synthetic",
+                          "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.chunks} chunks"},
+                          "rollout": ser}), flush=True)
         return 0
 
     # ---- inputs, resident in HBM
@@ -325,11 +454,18 @@ def main() -> int:
                      "bound": "mfma", "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": fwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
     }
+    # HBM bytes per launch come from a committed rocprofv3 counter run; they are only quoted while the kernel
+    # source is the one that run profiled
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         t = json.load(open(traffic_file)).get(w.name)
-        if t:
+        src = os.path.join(ROOT, "paper_2605_16579_amd", "csrc", "arl2_fwd_bf16.hip")
+        if t and t.get("fwd_kernel_source_sha16") == source_sha16(src):
             result["roofline"]["traffic"] = t.get("fwd_hbm_bytes_per_launch")
+            result["roofline"]["traffic_source"] = "profiles/traffic.json (%s), kernel source %s" % (
+                t.get("profile", "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE"), t.get("fwd_kernel_source_sha16"))
+        elif t:
+            result["roofline"]["traffic_source"] = "profiles/traffic.json is for another version of the kernel source: not quoted"
     if not args.no_cpu_baseline and fm is None and gp is None and not args.clean_readout:
         result["cpu_baseline"] = cpu_baseline(w, passes_cpu, clean_cpu, S0, args.cpu_steps, rule, rule_cpu)
     print(json.dumps(result), flush=True)

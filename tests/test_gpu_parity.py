@@ -286,10 +286,11 @@ def test_rollout_step_latency_is_flat(lib):
           f"min/median {ms.min() / med:.3f}, least-squares drift over the rollout {slope * w.chunks / med * 100:+.2f} % of median",
           flush=True)
     print("[wan_rollout] ms per chunk:", " ".join(f"{x:.3f}" for x in ms), flush=True)
-    # a cost that grew with the history (a cache of past chunks) would show up as hundreds of per cent;
-    # the margins leave room for clock drift on a power-limited launch
-    assert slope * w.chunks < 0.10 * med, "per-chunk latency grows with the chunk index"
-    assert np.percentile(ms, 90) < 1.25 * med
+    # a cost that grew with the history (a cache of past chunks) would show up as hundreds of per cent; recorded
+    # series on this hardware: drift between -3.6 % and +0.5 % of the median over the rollout, 90th percentile
+    # within 1 % of the median, single slow chunks (the first one, clock changes) up to 5 % above it
+    assert slope * w.chunks < 0.03 * med, "per-chunk latency grows with the chunk index"
+    assert np.percentile(ms, 90) < 1.05 * med
     assert torch.isfinite(S).all()
 
 
@@ -866,6 +867,28 @@ def test_bench_stack_report_runs(lib):
     assert r["speedup"] > 1.0 and 0.0 < r["memory_ratio"] < 1.0
     t = r["per_call_ms"]["softmax_kv_pass_by_cached_chunks"]
     assert len(t) == 2 and t[1] > t[0] > 0.0
+
+
+def test_bench_stack_executed_agrees_with_weighted_sum(lib):
+    """The full-stack configuration executed (30 layers, KV caches appended to per chunk, every layer pass and commit
+    launched, 3 chunks here) against the weighted sum of separately timed calls: attention time within 5 %, and the
+    peak device memory of caches + states against the analytic byte count."""
+    import importlib.util, os
+    spec = importlib.util.spec_from_file_location("arl2_bench", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    d = torch.device("cuda:0")
+    est = bench.stack_report(lib, W, torch, d, chunks=3, reps=3)
+    ex = bench.stack_execute(lib, W, torch, d, chunks=3)
+    for name in ("hybrid_stack", "softmax_stack"):
+        ratio = ex[name]["attention_ms"] / est[name]["attention_ms"]
+        print(f"[stack] {name}: executed {ex[name]['attention_ms']:.1f} ms, weighted sum {est[name]['attention_ms']:.1f} ms, ratio {ratio:.3f}; "
+              f"peak memory {ex[name]['peak_memory_bytes'] / 1e9:.3f} GB, counted {est[name]['memory_bytes'] / 1e9:.3f} GB", flush=True)
+        assert abs(ratio - 1.0) <= 0.05, (name, ratio)
+        assert ex[name]["readout_calls"] == 3 * 4 * 30
+        # allocator granularity and the commit workspace (hybrid stack only) are all that may come on top
+        assert est[name]["memory_bytes"] <= ex[name]["peak_memory_bytes"] <= est[name]["memory_bytes"] + (64 << 20)
+    assert ex["speedup"] > 1.0
 
 
 def _sweep_shapes():
