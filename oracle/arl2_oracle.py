@@ -22,6 +22,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "arl2_oracle.c")
 _LIB = os.path.join(_HERE, "libarl2_oracle.so")
+_LIB_SAN = os.path.join(_HERE, "libarl2_oracle_san.so")
 _lib = None
 
 L2_EPS = 1e-6  # the paper gives no epsilon for L2Norm in Eq. (3); this is the chosen reading
@@ -36,11 +37,36 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(force: bool = False) -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (host code only), every finding
+    fatal.  A process that loads it must have the AddressSanitizer runtime loaded first (see sanitizer_env)."""
+    if force or not os.path.exists(_LIB_SAN) or os.path.getmtime(_LIB_SAN) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-Wall", "-Wextra", "-o", _LIB_SAN, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB_SAN
+
+
+def sanitizer_env(env: dict) -> dict:
+    """Environment for a child process that is to run the oracle from the sanitized library: the sanitizer
+    runtime goes in front of whatever is preloaded already, leaks of the interpreter itself are not reported."""
+    rt = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, stdout=subprocess.PIPE, text=True).stdout.strip()
+    out = dict(env)
+    out["LD_PRELOAD"] = rt + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    out["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1"
+    out["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1"
+    out["ARL2_ORACLE_SANITIZED"] = "1"
+    return out
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        if os.environ.get("ARL2_ORACLE_SANITIZED") == "1":
+            lib = ctypes.CDLL(build_sanitized())
+        else:
+            build()
+            lib = ctypes.CDLL(_LIB)
         i32, f64, f32, vp = ctypes.c_int, ctypes.c_double, ctypes.c_float, ctypes.c_void_p
         lib.arl2o_fwd_f64.argtypes = [i32] * 5 + [vp] * 5 + [f64, f64, vp, i32, vp]
         lib.arl2o_fwd_f64.restype = i32

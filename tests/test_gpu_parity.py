@@ -507,7 +507,7 @@ def test_readout_with_own_linear_query(lib, oracle, io):
     prec = "f64"
     ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(g), q_lin=to_np(q_lin), precision=prec)
     e = rel_err(to_np(out), ref)
-    tol = TOL_BF16_OUT if io == "bf16" else 1e-4
+    tol = TOL_BF16_OUT if io == "bf16" else TOL_F32
     assert e <= tol, f"{io}: {e:.3e}"
     # q_lin = None and q_lin = q are the plain entry point, bit for bit
     o1, o2, o3 = (torch.empty_like(q, device="cuda") for _ in range(3))
@@ -731,7 +731,7 @@ def test_elementwise_gate(lib, oracle, io, gdt):
     torch.cuda.synchronize()
     ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(ge))
     e = rel_err(to_np(out), ref)
-    assert e <= (TOL_BF16_OUT if io == "bf16" else 1e-4), f"{io}/{gdt}: {e:.3e}"
+    assert e <= (TOL_BF16_OUT if io == "bf16" else TOL_F32), f"{io}/{gdt}: {e:.3e}"
     # constant over the features it is the headwise gate, bit for bit
     gc = g_head[..., None].expand(-1, -1, -1, w.D).contiguous()
     o1, o2 = torch.empty_like(out), torch.empty_like(out)
@@ -764,9 +764,9 @@ def test_scalar_gate(lib, oracle, io, gdt):
     torch.cuda.synchronize()
     ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(gt))   # the gate values the GPU read
     e = rel_err(to_np(out), ref)
-    assert e <= (TOL_BF16_OUT if io == "bf16" else 1e-4), f"{io}/{gdt}: {e:.3e}"
+    assert e <= (TOL_BF16_OUT if io == "bf16" else TOL_F32), f"{io}/{gdt}: {e:.3e}"
     ref2 = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), g_ref.astype(np.float32))   # the oracle's own gates
-    assert rel_err(to_np(out), ref2) <= (TOL_BF16_OUT if io == "bf16" else 1e-4)
+    assert rel_err(to_np(out), ref2) <= (TOL_BF16_OUT if io == "bf16" else TOL_F32)
     # repeated for every head it is the headwise gate, bit for bit
     gh = gt[..., None].expand(-1, -1, w.H).contiguous()
     o2 = torch.empty_like(out)

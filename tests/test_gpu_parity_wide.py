@@ -1,0 +1,278 @@
+"""GPU parity, second file: full tensors at the full sizes, the paper-derived hand example through the C ABI,
+non-default descriptor values, mid-range gates, resuming a rollout from a saved state.  As in
+test_gpu_parity.py everything goes through the ctypes binding of the C ABI and is compared with the CPU oracle."""
+import dataclasses
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from helpers import TOL_BF16_OUT, TOL_F32, TOL_STATE, rel_err, rel_err_per_head, to_np
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "hand_example.json")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_16579_amd as A
+    A.load_library()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return A
+
+
+def dev(t):
+    return t.cuda() if t is not None else None
+
+
+def error_figures(got, ref):
+    """The three error figures reported per tensor: max |gpu - ref| / max |ref| (the parity bar), the largest
+    element-wise |gpu - ref| / (|ref| + 1e-3 rms(ref)), and the relative root-mean-square error."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert np.isfinite(got).all()
+    diff = np.abs(got - ref)
+    rms = np.sqrt(np.mean(ref * ref))
+    return (float(diff.max() / max(np.abs(ref).max(), 1e-300)), float((diff / (np.abs(ref) + 1e-3 * rms)).max()),
+            float(np.sqrt(np.mean(diff * diff)) / max(rms, 1e-300)))
+
+
+def prefilled_state(oracle, w, n):
+    """fp64 state after n random commits (the oracle's own chain) and its fp32 copy for the GPU."""
+    S = np.zeros((w.B, w.H, w.D, w.D))
+    for j in range(n):
+        k, v, gate = W.prefill_inputs(w, j)
+        S = oracle.commit(to_np(k), to_np(v), to_np(gate), S)
+    return S, torch.from_numpy(S.astype(np.float32))
+
+
+def fwd_gpu(lib, q, k, v, S, g, **kw):
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd(dev(q), dev(k), dev(v), dev(S), dev(g), out, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def test_wan_layer_full_tensor(lib, oracle):
+    """Headline shape, every element of the output: one combined pass and the softmax branch alone."""
+    w = W.WORKLOADS["wan_layer"]
+    S64, S32 = prefilled_state(oracle, w, 2)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    for name, S_o, S_g, g_ in (("combined", S64, S32, g), ("softmax branch alone", None, None, None)):
+        ref = oracle.fwd(to_np(q), to_np(k), to_np(v), S_o, None if g_ is None else to_np(g_))
+        fig = error_figures(to_np(fwd_gpu(lib, q, k, v, S_g, g_)), ref)
+        print(f"[wan_layer full tensor, {name}] max-norm {fig[0]:.3e}, element-wise {fig[1]:.3e}, relative rms {fig[2]:.3e}", flush=True)
+        assert fig[0] <= TOL_BF16_OUT, (name, fig)
+        assert fig[2] <= 5e-3, (name, fig)              # one bf16 rounding of the output is 2^-9 at most per element
+
+
+def test_wan_batched_full_tensor_all_passes(lib, oracle):
+    """Eight streams, the configuration's eight prefill commits, all four passes: pass 0 in full (combined) plus
+    the softmax branch alone on a stream sample; passes 1-3 on sampled rows; then the commit in full."""
+    w = W.WORKLOADS["wan_batched"]
+    S64, S32 = prefilled_state(oracle, w, w.prefill)
+    S_dev = S32.cuda()
+    rows = np.unique(np.concatenate([np.arange(0, w.L, 197), [31, 32, 255, 256, 4607, 4608, w.L - 1]])).astype(np.int32)
+    for p in range(w.passes):
+        q, k, v, g = W.pass_inputs(w, 0, p)
+        got = to_np(fwd_gpu(lib, q, k, v, S_dev.cpu(), g))
+        if p == 0:
+            ref = oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g))
+            fig = error_figures(got, ref)
+            print(f"[wan_batched full tensor] max-norm {fig[0]:.3e}, element-wise {fig[1]:.3e}, relative rms {fig[2]:.3e}", flush=True)
+            assert fig[0] <= TOL_BF16_OUT and fig[2] <= 5e-3, fig
+            gi = to_np(fwd_gpu(lib, q, k, v, None, None))[:, rows]
+            e = rel_err(gi, oracle.fwd(to_np(q), to_np(k), to_np(v), rows=rows))
+            assert e <= TOL_BF16_OUT, f"softmax branch alone: {e:.3e}"
+        else:
+            e = rel_err(got[:, rows], oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g), rows=rows))
+            assert e <= TOL_BF16_OUT, f"pass {p}: {e:.3e}"
+    kc, vc, gate = W.clean_inputs(w, 0)
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    lib.arl2_state_commit(dev(kc), dev(vc), dev(gate), S_dev, ws)
+    torch.cuda.synchronize()
+    e = rel_err_per_head(to_np(S_dev), oracle.commit(to_np(kc), to_np(vc), to_np(gate), S64))
+    assert e <= TOL_STATE, f"state after the chunk: {e:.3e}"
+
+
+def test_softmax_over_full_kv_cache_full_tensor(lib, oracle):
+    """A softmax layer of the full-stack configuration at the end of the horizon: 4680 queries over a cache of
+    32760 keys, every output element."""
+    w = W.WORKLOADS["wan_layer"]
+    wk = dataclasses.replace(w, name="kv_cache_full", L=7 * w.L)
+    q = W.pass_inputs(w, 3, 0)[0]
+    k = W.normal(0, wk, (1, wk.L, w.H, w.D), 0, 0, 201)
+    v = W.normal(0, wk, (1, wk.L, w.H, w.D), 0, 0, 202)
+    fig = error_figures(to_np(fwd_gpu(lib, q, k, v, None, None)), oracle.fwd(to_np(q), to_np(k), to_np(v)))
+    print(f"[kv cache 4680 x 32760 full tensor] max-norm {fig[0]:.3e}, element-wise {fig[1]:.3e}, relative rms {fig[2]:.3e}", flush=True)
+    assert fig[0] <= TOL_BF16_OUT and fig[2] <= 5e-3, fig
+
+
+def _golden(val):
+    return float(np.log(3.0) / 3.0) if val == "ln3/3" else float(val)
+
+
+def test_hand_example_through_the_c_abi(lib):
+    """The hand-derived example of the paper's equations (tests/golden/hand_example.json), zero-padded from a
+    2-dimensional to a 64-dimensional head, through the C ABI in fp32: the HIP path against numbers that come from
+    the paper's equations alone, no oracle in between.  sm_scale = 1 and a negligible l2_eps as in the derivation."""
+    gold = json.load(open(GOLDEN))
+    f = gold["fwd"]
+    D = 64
+
+    def pad(rows):                       # [n][2] -> [1, n, 1, D]
+        a = np.zeros((1, len(rows), 1, D), np.float32)
+        for i, r in enumerate(rows):
+            a[0, i, 0, :2] = [_golden(x) for x in r]
+        return torch.from_numpy(a)
+    S = np.zeros((1, 1, D, D), np.float32)
+    S[0, 0, :2, :2] = f["S"]
+    # the boundary wants as many queries as keys when a state is given: the example's single query, twice
+    q2 = pad(f["q"] + f["q"])
+    g = torch.tensor(f["g"] + f["g"], dtype=torch.float32).reshape(1, 2, 1)
+    out = to_np(fwd_gpu(lib, q2, pad(f["k"]), pad(f["v"]), torch.from_numpy(S), g, sm_scale=f["sm_scale"], l2_eps=1e-30))
+    assert np.array_equal(out[0, 0], out[0, 1])
+    assert np.allclose(out[0, 0, 0, :2], f["out"][0], rtol=0, atol=2e-6), out[0, 0, 0, :4]
+    assert np.all(out[0, 0, 0, 2:] == 0.0)
+    intra = to_np(fwd_gpu(lib, q2, pad(f["k"]), pad(f["v"]), None, None, sm_scale=f["sm_scale"]))
+    assert np.allclose(intra[0, 0, 0, :2], f["O_intra"][0], rtol=0, atol=2e-6)
+    # the commits of the same file
+    c = gold["commit"]
+    ws = lib.alloc_workspace(1, 1, 2, D, torch.float32)
+    Sd = torch.zeros((1, 1, D, D), dtype=torch.float32, device="cuda")
+    Sd[0, 0, :2, :2] = torch.tensor(c["S_old"])
+    lib.arl2_state_commit(dev(pad(c["k"])), dev(pad(c["v"])), torch.tensor([[c["gate"]]], dtype=torch.float32, device="cuda"), Sd, ws, l2_eps=1e-30)
+    torch.cuda.synchronize()
+    assert np.allclose(to_np(Sd)[0, 0, :2, :2], c["S_new"], rtol=0, atol=5e-6), to_np(Sd)[0, 0, :2, :2]
+    assert float(Sd[0, 0, 2:, :].abs().max()) == 0.0 and float(Sd[0, 0, :, 2:].abs().max()) == 0.0
+    # bf16 path (all the example's inputs but ln3/3 are bf16 numbers): delta rule and token-sequential rule exist in bf16 only
+    cd = gold["commit_delta"]
+    wsb = lib.alloc_workspace(1, 1, 2, D, torch.bfloat16)
+    Sd.zero_()
+    Sd[0, 0, :2, :2] = torch.tensor(cd["S_old"])
+    lib.arl2_state_commit_delta(dev(pad(cd["k"]).bfloat16()), dev(pad(cd["v"]).bfloat16()), torch.tensor([[cd["alpha"]]], dtype=torch.float32, device="cuda"),
+                                torch.tensor([[cd["beta"]]], dtype=torch.float32, device="cuda"), Sd, wsb, l2_eps=1e-30)
+    torch.cuda.synchronize()
+    assert np.allclose(to_np(Sd)[0, 0, :2, :2], cd["S_new"], rtol=0, atol=2e-4), to_np(Sd)[0, 0, :2, :2]
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_non_default_scale_and_epsilon(lib, oracle, io):
+    """A softmax scale other than 1/sqrt(D) and an L2Norm epsilon large enough to change every row norm."""
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"knobs_{io}", io_dtype=io, L=300)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    S64, S32 = prefilled_state(oracle, w, 2)
+    tol_o, tol_s = (TOL_BF16_OUT, TOL_STATE) if io == "bf16" else (TOL_F32, TOL_F32)
+    for sm_scale, eps in ((0.25, 1e-6), (0.02, 3.0), (0.0883, 50.0)):
+        ref = oracle.fwd(to_np(q), to_np(k), to_np(v), S64, to_np(g), sm_scale=sm_scale, l2_eps=eps)
+        e = rel_err(to_np(fwd_gpu(lib, q, k, v, S32, g, sm_scale=sm_scale, l2_eps=eps)), ref)
+        assert e <= tol_o, f"sm_scale {sm_scale} l2_eps {eps}: {e:.3e}"
+        # must differ from the default call: the knobs reach the kernel
+        assert rel_err(to_np(fwd_gpu(lib, q, k, v, S32, g)), ref) > 3 * tol_o
+        kc, vc, gate = W.clean_inputs(w, 0)
+        Sd = S32.cuda()
+        ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, kc.dtype)
+        lib.arl2_state_commit(dev(kc), dev(vc), dev(gate), Sd, ws, l2_eps=eps)
+        torch.cuda.synchronize()
+        e = rel_err_per_head(to_np(Sd), oracle.commit(to_np(kc), to_np(vc), to_np(gate), S64, l2_eps=eps))
+        assert e <= tol_s, f"commit l2_eps {eps}: {e:.3e}"
+
+
+def test_gdn_commit_mid_range_forget_gates(lib, oracle):
+    """Token-sequential rule with per-token forget gates spread over (0.5, 1) (a block's gates multiply to ~1e-9,
+    so almost nothing of the state survives three blocks) and learning rates over (0.05, 0.95); several blocks,
+    a ragged last one, two chained updates."""
+    for D, L in ((128, 64 * 5 + 17), (64, 64 * 3 + 1)):
+        w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"gdn_mid{D}", D=D, L=L)
+        S0 = W.normal(5, w, (w.B, w.H, w.D, w.D), 0, 0, 93, io_dtype="f32")
+        S_ref, S_dev = to_np(S0).astype(np.float64), dev(S0).clone()
+        ws = torch.empty(lib.arl2_gdn_workspace_bytes(w.B, w.H, w.L, w.D), dtype=torch.uint8, device="cuda")
+        for c in range(2):
+            k, v, _ = W.clean_inputs(w, c)
+            alpha = W.uniform(1, w, (w.B, w.L, w.H), 0.5, 1.0, c, 0, 94)
+            beta = W.uniform(1, w, (w.B, w.L, w.H), 0.05, 0.95, c, 0, 95)
+            S_ref = oracle.commit_gdn(to_np(k), to_np(v), to_np(alpha), to_np(beta), S_ref)
+            lib.arl2_state_commit_gdn(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+            torch.cuda.synchronize()
+            e = rel_err_per_head(to_np(S_dev), S_ref)
+            assert e <= TOL_STATE, f"D={D} L={L} update {c}: {e:.3e}"
+
+
+@pytest.mark.parametrize("D,L", [(128, 328), (64, 100), (128, 4680)])
+def test_single_delta_update_with_large_learning_rate(lib, oracle, D, L):
+    """One frame-level delta-rule update at beta ~ U(0.1, 0.9) per head: a single update is well defined for any
+    learning rate (only a chain of them needs beta below 2 D / L to stay bounded)."""
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"delta_big_beta{D}", D=D, L=L, B=1 if L > 1000 else 2)
+    S0 = W.normal(5, w, (w.B, w.H, w.D, w.D), 0, 0, 96, io_dtype="f32")
+    k, v, alpha = W.clean_inputs(w, 0)
+    beta = W.uniform(2, w, (w.B, w.H), 0.1, 0.9, 0, 0, 97)
+    ref = oracle.commit_delta(to_np(k), to_np(v), to_np(alpha), to_np(beta), to_np(S0).astype(np.float64))
+    S_dev = dev(S0).clone()
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    lib.arl2_state_commit_delta(dev(k), dev(v), dev(alpha), dev(beta), S_dev, ws)
+    torch.cuda.synchronize()
+    e = rel_err_per_head(to_np(S_dev), ref)
+    assert e <= TOL_STATE, f"D={D} L={L}: {e:.3e}"
+
+
+@pytest.mark.parametrize("D,L", [(128, 328), (64, 200)])
+def test_fused_feature_map_against_the_unrounded_chain(lib, oracle, D, L):
+    """arl2_hybrid_attn_fwd_fm against the oracle chain with NO rounding between the feature map and the readout
+    (the bf16 rounding of the mapped query happens inside the kernel, so the reference must not mirror it)."""
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"fm_unrounded{D}", D=D, L=L)
+    q, k, v, g = W.pass_inputs(w, 0, 0)
+    xq = W.normal(22, w, (w.B, w.L, w.H, w.D), 0, 0, 104)
+    Wq, _, _ = W.feature_weights(w)
+    cs, sn = W.rope_tables(w)
+    S = W.normal(23, w, (w.B, w.H, w.D, w.D), 0, 0, 105, io_dtype="f32") * 0.2
+    out = torch.empty_like(q, device="cuda")
+    lib.arl2_hybrid_attn_fwd_fm(dev(q), dev(k), dev(v), dev(xq), dev(Wq), dev(cs), dev(sn), dev(S), dev(g), out)
+    torch.cuda.synchronize()
+    ql = oracle.feature_map(to_np(xq), to_np(Wq), to_np(cs), to_np(sn))          # fp64 values, passed on as they are
+    ref = oracle.fwd(to_np(q), to_np(k), to_np(v), to_np(S).astype(np.float64), to_np(g), q_lin=ql)
+    fig = error_figures(to_np(out), ref)
+    print(f"[fused map vs unrounded chain D={D}] max-norm {fig[0]:.3e}, relative rms {fig[2]:.3e}", flush=True)
+    assert fig[0] <= TOL_BF16_OUT, fig
+
+
+def test_rollout_resumes_bitwise_from_a_saved_state(lib):
+    """The state is all that carries across chunks: a 64-chunk rollout interrupted after chunk 32 (state copied to
+    the host, every device buffer reallocated) and resumed gives bit for bit the state and the outputs of the
+    uninterrupted run."""
+    w = W.WORKLOADS["wan_rollout"]
+    pool = 3
+    sets = [[tuple(dev(t) for t in W.pass_inputs(w, i, p)) for p in range(2)] for i in range(pool)]
+    cleans = [tuple(dev(t) for t in W.clean_inputs(w, i)) for i in range(pool)]
+    gates = [dev(W.uniform(0, w, (w.B, w.H), w.gate_lo, w.gate_hi, c, 0, W._GATE)) for c in range(w.chunks)]
+
+    def run(S, first, last, keep):
+        ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+        out = torch.empty_like(sets[0][0][0])
+        kept = {}
+        for c in range(first, last):
+            for p in range(2):
+                q, k, v, g = sets[c % pool][p]
+                lib.arl2_hybrid_attn_fwd(q, k, v, S, g, out)
+            if c in keep:
+                kept[c] = out.clone()
+            kc, vc, _ = cleans[c % pool]
+            lib.arl2_state_commit(kc, vc, gates[c], S, ws)
+        torch.cuda.synchronize()
+        return kept
+
+    keep = (33, 63)
+    S_a = torch.zeros((w.B, w.H, w.D, w.D), dtype=torch.float32, device="cuda")
+    kept_a = run(S_a, 0, w.chunks, keep)
+    S_b = torch.zeros_like(S_a)
+    run(S_b, 0, 32, ())
+    saved = S_b.cpu().numpy().copy()                       # the checkpoint: H x D x D floats per layer
+    del S_b
+    torch.cuda.empty_cache()
+    S_c = torch.from_numpy(saved).cuda()
+    kept_c = run(S_c, 32, w.chunks, keep)
+    assert torch.equal(S_a, S_c), "resumed state differs"
+    for c in keep:
+        assert torch.equal(kept_a[c], kept_c[c]), f"outputs of chunk {c} differ after the resume"
+    assert torch.isfinite(S_a).all()

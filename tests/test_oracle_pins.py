@@ -588,3 +588,23 @@ def test_gate_granularities(oracle):
     from scipy.special import expit
     x, w1 = rand(B, L, H * D), rand(1, H * D, scale=0.3)
     np.testing.assert_allclose(oracle.gate_proj(x, w1)[..., 0], expit(x.astype(np.float64) @ w1[0].astype(np.float64)), rtol=1e-13)
+
+
+def test_pins_hold_under_address_and_undefined_behaviour_sanitizers():
+    """The whole pin suite once more in a child process whose oracle is built with -fsanitize=address,undefined
+    (every finding aborts): an out-of-bounds index or a signed overflow in the oracle's loops fails here even
+    where it happens not to change a pinned value."""
+    import os
+    import subprocess
+    import sys
+    from oracle import arl2_oracle as O
+    if os.environ.get("ARL2_ORACLE_SANITIZED") == "1":
+        return                                      # this is the child
+    O.build_sanitized()
+    env = O.sanitizer_env(os.environ)
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"],
+                         env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=900,
+                         cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    tail = "\n".join(res.stdout.splitlines()[-25:])
+    assert res.returncode == 0, tail
+    assert " passed" in tail and "failed" not in tail, tail
