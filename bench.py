@@ -254,7 +254,8 @@ def main() -> int:
                          "q_lin = RoPE(phi_q(Q)) (arl2_feature_map) and reads the state with it; the commit is preceded by "
                          "RoPE(phi_k(K)) and phi_v(V) of the clean pass.  Not the headline configuration.")
     ap.add_argument("--unfused-maps", action="store_true",
-                    help="with --feature-maps: compute q_lin with a separate arl2_feature_map launch instead of inside the readout")
+                    help="with --feature-maps: every map as a separate arl2_feature_map launch instead of inside the readout "
+                         "and (plain rule) the commit kernel")
     ap.add_argument("--gate-proj", action="store_true",
                     help="compute the mix gate of every readout pass on the path, G = sigmoid(x W_g) (arl2_gate_proj), "
                          "instead of taking it as an input.  Not the headline configuration.")
@@ -361,6 +362,10 @@ def main() -> int:
               "kl": torch.empty_like(kc), "vl": torch.empty_like(kc)}
 
     def commit():
+        if fm is not None and rule == "plain" and not args.unfused_maps:
+            # the key and value maps run inside the commit kernel: no intermediate arrays, no extra launches
+            A.arl2_state_commit_fm(kc, fm["Wk"], fm["cs"], fm["sn"], vc, fm["Wv"], gate, S, ws)
+            return
         if fm is not None:
             A.arl2_feature_map(kc, fm["Wk"], fm["cs"], fm["sn"], fm["kl"])
             A.arl2_feature_map(vc, fm["Wv"], None, None, fm["vl"])
@@ -440,7 +445,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.io_dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} D={w.D} L={w.L}, {w.passes} readout passes + 1 commit per step",
-                   "passes": w.passes, "commit_rule": rule, "feature_maps": ("fused query map" if not args.unfused_maps else "separate launches") if args.feature_maps else False, "gate_proj": args.gate_granularity if args.gate_proj else False,
+                   "passes": w.passes, "commit_rule": rule, "feature_maps": (("query map fused into the readout" + (", key and value maps fused into the commit" if rule == "plain" else ""))
+                                    if not args.unfused_maps else "separate launches") if args.feature_maps else False, "gate_proj": args.gate_granularity if args.gate_proj else False,
                    "readouts_per_step": n_read, "state": "fp32 [B,H,D,D], pre-filled by %d commits" % w.prefill},
         "step_tflops": step_tflops,
         "step_frac_bf16_peak": step_tflops / PEAK_BF16_TFLOPS,

@@ -199,6 +199,30 @@ arl2_status arl2_state_commit_static(const arl2_desc *desc,
                                      const float *gate, float *S);
 
 /*
+ * arl2_state_commit with the key and value feature maps of the linear branch fused in (paper Eq. (3),
+ * Eq. (4); Alg. 1 clean pass):
+ *     S <- gate * S + sum_i L2Norm(RoPE_i(Wk[h] xk_i))^T (Wv[h] xv_i)
+ * equal to arl2_feature_map(xk, Wk, rope_cos, rope_sin), arl2_feature_map(xv, Wv, NULL, NULL) and
+ * arl2_state_commit on their outputs, without the two intermediate arrays and their launches.  The mapped
+ * key is rounded to bf16 once, as arl2_feature_map would store it, and normalised as rounded; the mapped
+ * value stays in fp32 until it is scaled by the key's inverse norm (it is not rounded to bf16 on its own,
+ * so the result is closer to exact arithmetic than the three calls, not bit-identical to them).
+ *   xk, xv    device bf16 [B][Lq][H][D]: the clean pass's projections the maps act on (desc->io_dtype must
+ *             be ARL2_BF16, desc->Lkv must equal Lq).
+ *   Wk, Wv    device bf16 [H][D][D], indexed [head][out][in], as in arl2_feature_map.
+ *   rope_cos, rope_sin   device fp32 [Lq][D/2], 8-byte aligned: the key map's rotation, as in
+ *             arl2_feature_map; both NULL: no rotation.  The value map is never rotated.
+ *   gate      device fp32 [B][H].
+ *   S         device fp32 [B][H][D][D], updated IN PLACE.
+ * Deterministic.  Uses desc->workspace (arl2_workspace_bytes covers it).
+ */
+arl2_status arl2_state_commit_fm(const arl2_desc *desc,
+                                 const void *xk, const void *Wk,
+                                 const float *rope_cos, const float *rope_sin,
+                                 const void *xv, const void *Wv,
+                                 const float *gate, float *S);
+
+/*
  * Post-denoise state update with the delta-correction term: paper Eq. (4) taken literally at
  * frame level,
  *     S <- alpha * S + beta * K'^T (V - K' S),      K' = L2Norm(k) per token (Eq. (3)),

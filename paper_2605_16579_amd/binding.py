@@ -20,7 +20,7 @@ ARL2_F32, ARL2_BF16 = 0, 1
 ARL2_GATE_PER_HEAD, ARL2_GATE_PER_ELEMENT, ARL2_GATE_PER_TOKEN = 0, 1, 2
 
 EXPORTS = ["arl2_workspace_bytes", "arl2_hybrid_attn_fwd", "arl2_state_commit", "arl2_state_commit_delta",
-           "arl2_static_scratch_bytes", "arl2_state_commit_static",
+           "arl2_static_scratch_bytes", "arl2_state_commit_static", "arl2_state_commit_fm",
            "arl2_gdn_workspace_bytes", "arl2_state_commit_gdn", "arl2_hybrid_attn_fwd_ex", "arl2_hybrid_attn_fwd_fm", "arl2_feature_map", "arl2_gate_proj",
            "arl2_status_string", "arl2_last_error", "arl2_version"]
 
@@ -62,6 +62,8 @@ def load_library() -> ctypes.CDLL:
         lib.arl2_state_commit_static.restype = ctypes.c_int
         lib.arl2_static_scratch_bytes.argtypes = []
         lib.arl2_static_scratch_bytes.restype = ctypes.c_size_t
+        lib.arl2_state_commit_fm.argtypes = [dp] + [vp] * 8
+        lib.arl2_state_commit_fm.restype = ctypes.c_int
         lib.arl2_state_commit_delta.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.arl2_state_commit_delta.restype = ctypes.c_int
         lib.arl2_hybrid_attn_fwd_ex.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
@@ -280,6 +282,22 @@ def arl2_state_commit_static(k: torch.Tensor, v: torch.Tensor, gate: torch.Tenso
     d = make_desc(B, H, L, L, D, _dtype_code(k), ARL2_F32, 0.0, l2_eps, stream=stream)
     st = load_library().arl2_state_commit_static(
         ctypes.byref(d), _dev(k, "k"), _dev(v, "v", (B, L, H, D), k.dtype),
+        _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
+    _check(st)
+
+
+def arl2_state_commit_fm(xk: torch.Tensor, Wk: torch.Tensor, rope_cos: Optional[torch.Tensor], rope_sin: Optional[torch.Tensor],
+                         xv: torch.Tensor, Wv: torch.Tensor, gate: torch.Tensor, S: torch.Tensor,
+                         workspace: torch.Tensor, *, l2_eps: float = 0.0, stream: Optional[int] = None) -> None:
+    """``arl2_state_commit`` on RoPE(Wk xk) and Wv xv, the two feature maps computed inside the commit kernel."""
+    if xk.dim() != 4:
+        raise ValueError("xk must be [B, L, H, D]")
+    B, L, H, D = xk.shape
+    d = make_desc(B, H, L, L, D, _dtype_code(xk), ARL2_F32, 0.0, l2_eps, workspace=workspace, stream=stream)
+    st = load_library().arl2_state_commit_fm(
+        ctypes.byref(d), _dev(xk, "xk"), _dev(Wk, "Wk", (H, D, D), xk.dtype),
+        _dev(rope_cos, "rope_cos", (L, D // 2), torch.float32), _dev(rope_sin, "rope_sin", (L, D // 2), torch.float32),
+        _dev(xv, "xv", (B, L, H, D), xk.dtype), _dev(Wv, "Wv", (H, D, D), xk.dtype),
         _dev(gate, "gate", (B, H), torch.float32), _dev(S, "S", (B, H, D, D), torch.float32))
     _check(st)
 

@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libarl2_hip.so")
-SOURCES = ["arl2_api.hip", "arl2_fwd_bf16.hip", "arl2_commit_bf16.hip", "arl2_gdn_bf16.hip", "arl2_fmap_bf16.hip", "arl2_gate_bf16.hip", "arl2_f32.hip"]
+SOURCES = ["arl2_api.hip", "arl2_fwd_bf16.hip", "arl2_commit_bf16.hip", "arl2_commit_fm_bf16.hip", "arl2_gdn_bf16.hip", "arl2_fmap_bf16.hip", "arl2_gate_bf16.hip", "arl2_f32.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -299,6 +299,53 @@ arl2_status arl2_state_commit_delta(const arl2_desc *desc, const void *k, const 
     return commit_common(desc, k, v, gate, beta, true, S);
 }
 
+arl2_status arl2_state_commit_fm(const arl2_desc *desc, const void *xk, const void *Wk,
+                                 const float *rope_cos, const float *rope_sin,
+                                 const void *xv, const void *Wv, const float *gate, float *S)
+{
+    arl2_status st = check_desc(desc);
+    if (st != ARL2_OK) return st;
+    if (!xk || !Wk || !xv || !Wv || !gate || !S)
+        return fail(ARL2_ERR_INVALID_ARG, "xk, Wk, xv, Wv, gate and S must not be NULL");
+    if (!aligned16(xk) || !aligned16(Wk) || !aligned16(xv) || !aligned16(Wv) || !aligned16(S))
+        return fail(ARL2_ERR_INVALID_ARG, "xk, Wk, xv, Wv and S must be 16-byte aligned");
+    if ((rope_cos == nullptr) != (rope_sin == nullptr))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
+    if ((reinterpret_cast<uintptr_t>(rope_cos) & 7u) || (reinterpret_cast<uintptr_t>(rope_sin) & 7u))
+        return fail(ARL2_ERR_INVALID_ARG, "rope_cos and rope_sin must be 8-byte aligned");
+    if (reinterpret_cast<uintptr_t>(gate) & 3u) return fail(ARL2_ERR_INVALID_ARG, "gate must be 4-byte aligned");
+    if (desc->Lkv != desc->Lq) return fail(ARL2_ERR_INVALID_ARG, "Lkv must equal Lq in a state commit");
+    if (desc->io_dtype != ARL2_BF16) return fail(ARL2_ERR_UNSUPPORTED, "arl2_state_commit_fm takes bf16 inputs only");
+    if (!fits_32bit(((double)desc->Lq + 256.0) * desc->H * desc->D, 2))
+        return fail(ARL2_ERR_UNSUPPORTED, "one stream's xk (or xv) must stay below 2 GiB");
+    const size_t need = commit_workspace_plain(desc);
+    if (desc->workspace == nullptr || desc->workspace_bytes < need)
+        return fail(ARL2_ERR_WORKSPACE, "workspace is NULL or smaller than arl2_workspace_bytes()");
+    if (!aligned16(desc->workspace)) return fail(ARL2_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    {
+        const size_t ns = state_bytes(desc), nx = kv_bytes(desc), ngate = (size_t)desc->B * desc->H * sizeof(float);
+        const size_t nw = wmap_bytes(desc), nt = table_bytes(desc);
+        const void *in[] = {xk, xv, Wk, Wv, rope_cos, rope_sin, gate};
+        const size_t nb[] = {nx, nx, nw, nw, nt, nt, ngate};
+        for (int i = 0; i < 7; ++i) {
+            if (overlaps(S, ns, in[i], nb[i])) return fail(ARL2_ERR_INVALID_ARG, "S must not overlap an input");
+            if (overlaps(desc->workspace, need, in[i], nb[i]))
+                return fail(ARL2_ERR_INVALID_ARG, "the workspace must not overlap an input");
+        }
+        if (overlaps(S, ns, desc->workspace, need)) return fail(ARL2_ERR_INVALID_ARG, "S must not overlap the workspace");
+    }
+
+    arl2::CommitFmArgs a;
+    a.xk = xk; a.xv = xv; a.Wk = Wk; a.Wv = Wv; a.cs = rope_cos; a.sn = rope_sin;
+    a.gate = gate; a.S = S; a.workspace = desc->workspace;
+    a.B = desc->B; a.H = desc->H; a.L = desc->Lq; a.D = desc->D;
+    a.nsplit = arl2::commit_nsplit(desc->B, desc->H, desc->Lq);
+    a.l2_eps = resolved_eps(desc);
+    const hipError_t e = arl2::launch_commit_fm_bf16(a, reinterpret_cast<hipStream_t>(desc->stream));
+    if (e != hipSuccess) return fail(ARL2_ERR_DEVICE, "commit launch failed: %s", hipGetErrorString(e));
+    return ARL2_OK;
+}
+
 size_t arl2_gdn_workspace_bytes(const arl2_desc *desc)
 {
     if (check_desc(desc) != ARL2_OK) return 0;

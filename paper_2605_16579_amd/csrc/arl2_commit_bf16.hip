@@ -471,6 +471,14 @@ int commit_nsplit(int B, int H, int L)
     return (int)want;
 }
 
+hipError_t launch_commit_reduce_bf16(const CommitArgs &a, hipStream_t stream)
+{
+    const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
+    const long long rwg = (long long)a.B * a.H * (vec_per_head / NTR);
+    if (rwg <= 0 || rwg > 0x7fffffffLL) return hipErrorInvalidValue;
+    return launch_kernel(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NTR), stream, a, vec_per_head);
+}
+
 hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
 {
     const long long nwg = (long long)a.B * a.H * a.nsplit;
@@ -496,9 +504,7 @@ hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream)
         if (a.D == 128) return launch_kernel(commit_delta_reduce_kernel<128>, dim3((unsigned)rwg), dim3(NTR), stream, a);
         return launch_kernel(commit_delta_reduce_kernel<64>, dim3((unsigned)rwg), dim3(NTR), stream, a);
     }
-    const int vec_per_head = a.D * a.D / 4;        // multiple of 256 for D in {64, 128}
-    const long long rwg = (long long)a.B * a.H * (vec_per_head / NTR);
-    return launch_kernel(commit_reduce_kernel<8>, dim3((unsigned)rwg), dim3(NTR), stream, a, vec_per_head);
+    return launch_commit_reduce_bf16(a, stream);
 }
 
 }  // namespace arl2

@@ -63,6 +63,18 @@ struct CommitArgs {
     float l2_eps;
 };
 
+struct CommitFmArgs {
+    const void *xk, *xv;   // [B][L][H][D] bf16, the projections the key and value maps act on
+    const void *Wk, *Wv;   // [H][D][D] bf16, [head][out][in]
+    const float *cs, *sn;  // [L][D/2] rotation tables of the key map, or both nullptr
+    const float *gate;
+    float *S;
+    void *workspace;
+    int B, H, L, D;
+    int nsplit;
+    float l2_eps;
+};
+
 struct FmapArgs {
     const void *x;         // [B][L][H][D] bf16
     const void *W;         // [H][D][D] bf16, indexed [head][out][in]
@@ -98,6 +110,9 @@ hipError_t launch_fwd_bf16(const FwdArgs &a, hipStream_t stream);
 hipError_t launch_fwd_f32(const FwdArgs &a, hipStream_t stream);
 hipError_t launch_commit_bf16(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_f32(const CommitArgs &a, hipStream_t stream);
+hipError_t launch_commit_fm_bf16(const CommitFmArgs &a, hipStream_t stream);
+// S = gate * S + the token-split partial sums in a.workspace ([B*H][nsplit][D][D] fp32), added in split order.
+hipError_t launch_commit_reduce_bf16(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_commit_gdn_bf16(const GdnArgs &a, hipStream_t stream);
 hipError_t launch_feature_map_bf16(const FmapArgs &a, hipStream_t stream);
 hipError_t launch_gate_proj_bf16(const GateArgs &a, hipStream_t stream);

@@ -115,6 +115,28 @@ def test_commit_rejects_bad_arguments_before_launch(A):
     assert gdn(df) == 2
 
 
+def test_fused_feature_map_commit_rejects_bad_arguments(A):
+    lib = A.load_library()
+    d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)
+    call = lambda d, xk=0x10000000, Wk=0x20000000, c=0x30000000, s=0x34000000, xv=0x40000000, Wv=0x50000000, gate=0x54000000, S=0x60000000: \
+        lib.arl2_state_commit_fm(ctypes.byref(d), xk, Wk, c, s, xv, Wv, gate, S)
+    assert call(d) == 3                                   # no workspace
+    d.workspace, d.workspace_bytes = 0x70000000, A.arl2_workspace_bytes(1, 2, 64, 64, A.ARL2_BF16)
+    assert call(d, Wv=None) == 1
+    assert call(d, xk=None) == 1
+    assert call(d, s=None) == 1                           # cosines without sines
+    assert call(d, c=0x30000004) == 1                     # tables must be 8-byte aligned
+    assert call(d, gate=0x54000002) == 1
+    assert call(d, S=0x10000400) == 1                     # S inside xk
+    assert b"overlap" in lib.arl2_last_error()
+    assert call(d, Wk=0x70000040) == 1                    # Wk inside the workspace
+    d.Lkv = 32
+    assert call(d) == 1
+    df = A.make_desc(1, 2, 64, 64, 64, A.ARL2_F32, stream=0)
+    df.workspace, df.workspace_bytes = 0x70000000, 1 << 20
+    assert call(df) == 2                                  # bf16 only
+
+
 def test_feature_map_and_fwd_ex_reject_bad_arguments(A):
     lib = A.load_library()
     d = A.make_desc(1, 2, 64, 64, 64, A.ARL2_BF16, stream=0)

@@ -227,6 +227,10 @@ def test_wan_rollout_64_chained_commits(lib, oracle):
             got = to_np(gpu_fwd(lib, q, k, v, S_dev, g))[:, rows]
             e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), S_ref, to_np(g), rows=rows))
             assert e <= TOL_BF16_OUT, f"chunk {c}: out {e:.3e}"
+            # the same rows with the state branch off: the softmax term alone
+            got = to_np(gpu_fwd(lib, q, k, v, None, None))[:, rows]
+            e = rel_err(got, oracle.fwd(to_np(q), to_np(k), to_np(v), rows=rows))
+            assert e <= TOL_BF16_OUT, f"chunk {c}: softmax-only out {e:.3e}"
         k, v, gate = W.clean_inputs(w, c)
         S_ref = oracle.commit(to_np(k), to_np(v), to_np(gate), S_ref)
         gpu_commit(lib, k, v, gate, S_dev)

@@ -237,6 +237,123 @@ def test_fused_feature_map_against_the_unrounded_chain(lib, oracle, D, L):
     assert fig[0] <= TOL_BF16_OUT, fig
 
 
+def _bf16_round(x):
+    return torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16)
+
+
+FM_SHAPES = [(128, 328, 2, 3), (64, 200, 1, 4), (128, 257, 1, 2), (128, 1, 1, 2), (64, 63, 2, 1), (128, 65, 1, 13),
+             (128, 4680, 1, 12)]
+
+
+def _exact_maps(w, seed):
+    """Feature maps whose outputs are exact in any arithmetic: every row of Wk and Wv has a single entry, a
+    signed power of two at a random column (a signed, scaled permutation per head), and every rotation is a
+    multiple of a quarter turn (cos, sin in {0, 1, -1}).  The mapped key then needs no rounding, so the kernel
+    and the oracle read the same bf16 key whatever their summation order."""
+    r = np.random.default_rng(seed)
+    def perm():
+        m = np.zeros((w.H, w.D, w.D), np.float32)
+        for h in range(w.H):
+            m[h, np.arange(w.D), r.permutation(w.D)] = r.choice([-1.0, 1.0], w.D) * 2.0 ** r.integers(-2, 3, w.D)
+        return torch.from_numpy(m).to(torch.bfloat16)
+    quarter = r.integers(0, 4, (w.L, w.D // 2))
+    cs = torch.from_numpy(np.array([1.0, 0.0, -1.0, 0.0], np.float32)[quarter]).contiguous()
+    sn = torch.from_numpy(np.array([0.0, 1.0, 0.0, -1.0], np.float32)[quarter]).contiguous()
+    return perm(), perm(), cs, sn
+
+
+@pytest.mark.parametrize("D,L,B,H", FM_SHAPES)
+def test_commit_with_fused_feature_maps_exact_maps(lib, oracle, D, L, B, H):
+    """arl2_state_commit_fm against the oracle chain feature_map -> feature_map -> commit (Eq. (3), (4)) with maps
+    that round nowhere: the state must agree to the fp32-state tolerance, at every shape up to the full size."""
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"commit_fm_exact{D}_{L}", D=D, L=L, B=B, H=H)
+    xk, xv, gate = W.clean_inputs(w, 0)
+    Wk, Wv, cs, sn = _exact_maps(w, 1000 + L)
+    S0 = W.normal(31, w, (B, H, D, D), 0, 0, 111, io_dtype="f32") * 0.2
+    S_dev = dev(S0).clone()
+    ws = lib.alloc_workspace(B, H, L, D, torch.bfloat16)
+    lib.arl2_state_commit_fm(dev(xk), dev(Wk), dev(cs), dev(sn), dev(xv), dev(Wv), dev(gate), S_dev, ws)
+    torch.cuda.synchronize()
+    f = to_np
+    kl64, vl64 = oracle.feature_map(f(xk), f(Wk), f(cs), f(sn)), oracle.feature_map(f(xv), f(Wv))
+    assert np.array_equal(kl64, to_np(_bf16_round(kl64)).astype(np.float64)), "the construction is meant to be exact"
+    ref = oracle.commit(kl64, vl64, f(gate), f(S0).astype(np.float64))
+    e = rel_err_per_head(to_np(S_dev), ref)
+    print(f"[commit_fm exact maps D={D} L={L} B={B} H={H}] state err {e:.3e}", flush=True)
+    assert e <= TOL_STATE, f"{e:.3e}"
+    assert not torch.equal(S_dev, dev(S0))
+
+
+@pytest.mark.parametrize("D,L,B,H", FM_SHAPES)
+@pytest.mark.parametrize("rope", [True, False])
+def test_commit_with_fused_feature_maps(lib, oracle, D, L, B, H, rope):
+    """arl2_state_commit_fm with dense maps against the oracle chain: feature maps in fp64, the mapped key rounded
+    to bf16 (the one quantisation the kernel applies: its contraction reads bf16 keys and it normalises what
+    it reads), the mapped value passed on unrounded, then the commit.  The kernel takes the rounding decision
+    on an fp32 sum, the oracle on an fp64 one: about one key entry in 20000 lands on the other side (one bf16
+    ulp, 2^-8 of that entry), and each such entry moves one row of one head's state by up to 2^-8 of a
+    single token's contribution.  So: every row within the bf16 bound, and the typical (median) row within the
+    fp32-state tolerance, which a systematic error would not pass."""
+    if not rope and L not in (257, 4680):
+        pytest.skip("the unrotated key map is covered at two shapes")
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name=f"commit_fm{D}_{L}", D=D, L=L, B=B, H=H)
+    xk, xv, gate = W.clean_inputs(w, 0)
+    _, Wk, Wv = W.feature_weights(w)
+    cs, sn = W.rope_tables(w) if rope else (None, None)
+    S0 = W.normal(31, w, (B, H, D, D), 0, 0, 111, io_dtype="f32") * 0.2
+    S_dev = dev(S0).clone()
+    ws = lib.alloc_workspace(B, H, L, D, torch.bfloat16)
+    lib.arl2_state_commit_fm(dev(xk), dev(Wk), dev(cs), dev(sn), dev(xv), dev(Wv), dev(gate), S_dev, ws)
+    torch.cuda.synchronize()
+    f = to_np
+    kl64 = oracle.feature_map(f(xk), f(Wk), None if cs is None else f(cs), None if sn is None else f(sn))
+    vl64 = oracle.feature_map(f(xv), f(Wv))
+    S64 = f(S0).astype(np.float64)
+    ref = oracle.commit(to_np(_bf16_round(kl64)), vl64, f(gate), S64)
+    got = to_np(S_dev).astype(np.float64)
+    row_err = np.abs(got - ref).max(axis=3) / np.abs(ref).max(axis=(2, 3), keepdims=True)[..., 0]     # [B][H][D]
+    e_unrounded = rel_err_per_head(got, oracle.commit(kl64, vl64, f(gate), S64))
+    print(f"[commit_fm D={D} L={L} B={B} H={H} rope={rope}] row err: median {np.median(row_err):.3e}, worst {row_err.max():.3e}, "
+          f"{(row_err > TOL_STATE).sum()} of {row_err.size} rows above {TOL_STATE:g}; against the unrounded chain {e_unrounded:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert row_err.max() <= 2e-3 and np.median(row_err) <= TOL_STATE and (row_err > TOL_STATE).mean() <= 0.01
+    assert e_unrounded <= 4e-3, f"{e_unrounded:.3e}"
+    # the three-call path computes the same update with one more rounding (the mapped value to bf16)
+    kl, vl = torch.empty_like(xk, device="cuda"), torch.empty_like(xk, device="cuda")
+    S3 = dev(S0).clone()
+    lib.arl2_feature_map(dev(xk), dev(Wk), dev(cs), dev(sn), kl)
+    lib.arl2_feature_map(dev(xv), dev(Wv), None, None, vl)
+    lib.arl2_state_commit(kl, vl, dev(gate), S3, ws)
+    # and the call is deterministic
+    S_again = dev(S0).clone()
+    lib.arl2_state_commit_fm(dev(xk), dev(Wk), dev(cs), dev(sn), dev(xv), dev(Wv), dev(gate), S_again, ws)
+    torch.cuda.synchronize()
+    assert rel_err_per_head(got, to_np(S3).astype(np.float64)) <= 4e-3
+    assert torch.equal(S_dev, S_again)
+
+
+def test_commit_with_fused_maps_edge_gates_and_identity(lib, oracle):
+    """Identity maps without rotation reduce the fused commit to the plain one on the same inputs (the key is
+    mapped exactly; the value keeps fp32, which for bf16 inputs is the input itself); a gate of zero forgets
+    the old state; eps and the stream's gate reach the kernel."""
+    w = dataclasses.replace(W.WORKLOADS["ragged_small"], name="commit_fm_id", D=128, L=200, B=1, H=3)
+    k, v, gate = W.clean_inputs(w, 0)
+    gate = gate.clone()
+    gate[0, 1] = 0.0
+    eye = torch.eye(w.D, dtype=torch.bfloat16).repeat(w.H, 1, 1).contiguous()
+    S0 = W.normal(32, w, (w.B, w.H, w.D, w.D), 0, 0, 112, io_dtype="f32")
+    ws = lib.alloc_workspace(w.B, w.H, w.L, w.D, torch.bfloat16)
+    S1, S2 = dev(S0).clone(), dev(S0).clone()
+    lib.arl2_state_commit_fm(dev(k), dev(eye), None, None, dev(v), dev(eye), dev(gate), S1, ws, l2_eps=50.0)
+    lib.arl2_state_commit(dev(k), dev(v), dev(gate), S2, ws, l2_eps=50.0)
+    torch.cuda.synchronize()
+    ref = oracle.commit(to_np(k), to_np(v), to_np(gate), to_np(S0).astype(np.float64), l2_eps=50.0)
+    assert rel_err_per_head(to_np(S1), ref) <= TOL_STATE
+    assert rel_err_per_head(to_np(S1), to_np(S2).astype(np.float64)) <= 1e-5
+    ref_default_eps = oracle.commit(to_np(k), to_np(v), to_np(gate), to_np(S0).astype(np.float64))
+    assert rel_err_per_head(to_np(S1), ref_default_eps) > 3 * TOL_STATE      # the epsilon is not ignored
+
+
 def test_rollout_resumes_bitwise_from_a_saved_state(lib):
     """The state is all that carries across chunks: a 64-chunk rollout interrupted after chunk 32 (state copied to
     the host, every device buffer reallocated) and resumed gives bit for bit the state and the outputs of the
