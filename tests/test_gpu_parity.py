@@ -811,7 +811,8 @@ def test_degenerate_rows(lib, oracle):
 @pytest.mark.parametrize("long_chunk", [False, True])
 def test_chunk_step_replays_from_a_captured_graph(lib, long_chunk):
     """The library neither allocates nor synchronises, so a whole chunk step (readout passes, feature map,
-    gate projection, all three commit rules) can be captured into a graph.  Every replay must reproduce the
+    gate projection, the commit with and without fused maps and from the static scratch array, the delta and the
+    token-sequential rule) can be captured into a graph.  Every replay must reproduce the
     eager result bit for bit, with eager work and synchronisations between the replays.  The long chunk
     makes the token-sequential commit walk its blocks as several runs (three launches)."""
     import dataclasses
@@ -822,7 +823,7 @@ def test_chunk_step_replays_from_a_captured_graph(lib, long_chunk):
     kc, vc, gate = (dev(t) for t in W.clean_inputs(w, 0))
     alpha, beta_t = (dev(t) for t in W.token_gates(w, 0))
     beta = torch.full((w.B, w.H), 0.1, device="cuda")
-    Wq, _, _ = (dev(t) for t in W.feature_weights(w))
+    Wq, Wk, Wv = (dev(t) for t in W.feature_weights(w))
     cs, sn = (dev(t) for t in W.rope_tables(w))
     xh, Wg = (dev(t) for t in W.gate_inputs(w, 0, 0))
     S0 = dev(W.normal(18, w, (w.B, w.H, w.D, w.D), 0, 0, 100, io_dtype="f32")) * 0.2
@@ -837,6 +838,8 @@ def test_chunk_step_replays_from_a_captured_graph(lib, long_chunk):
         lib.arl2_hybrid_attn_fwd_ex(q, k, v, ql, S, gg, out)
         lib.arl2_hybrid_attn_fwd_fm(q, k, v, q, Wq, cs, sn, S, gg, out_fm)
         lib.arl2_state_commit(kc, vc, gate, S, ws)
+        lib.arl2_state_commit_fm(kc, Wk, cs, sn, vc, Wv, gate, S, ws)
+        lib.arl2_state_commit_static(kc, vc, gate, S)
         lib.arl2_state_commit_delta(kc, vc, gate, beta, S, ws)
         lib.arl2_state_commit_gdn(kc, vc, alpha, beta_t, S, ws_gdn)
 
