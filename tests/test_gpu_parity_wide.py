@@ -241,8 +241,10 @@ def _bf16_round(x):
     return torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16)
 
 
+# (D, L, B, H): one tile per workgroup; ragged and single-token chunks; many heads (two token splits, 6-8 tiles per
+# workgroup: the steady state of the tile pipeline) at both head dimensions; the full size
 FM_SHAPES = [(128, 328, 2, 3), (64, 200, 1, 4), (128, 257, 1, 2), (128, 1, 1, 2), (64, 63, 2, 1), (128, 65, 1, 13),
-             (128, 4680, 1, 12)]
+             (64, 1000, 2, 48), (128, 777, 3, 32), (128, 4680, 1, 12)]
 
 
 def _exact_maps(w, seed):
