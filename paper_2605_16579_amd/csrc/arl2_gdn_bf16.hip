@@ -713,6 +713,237 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
     }
 }
 
+
+// ---- kernel 2, D = 128: the same walk with eight wavefronts per 64 state columns ------------------------------
+// A step of the walk is a chain (split S, contract, form R, contract, update S) that a single wavefront per
+// SIMD runs at the sum of its matrix-core and vector-ALU times.  Here two wavefronts share each SIMD and each
+// carries half of a step's work, so a SIMD issues the vector-ALU parts at twice the rate and every chain link
+// is half as long:
+//   * state: wavefront w owns rows 32 rbF .. + 31 (rbF = w % 2 + 2 (w / 4)) of column block cb = w / 2 % 2;
+//   * T = K S: the 32 x 32 block (token block rbT = w % 2, column block cb) belongs to the pair (w, w + 4);
+//     member m = w / 4 contracts over features 64 m .. 64 m + 63 (K raw against S hi and S lo, one accumulator),
+//     passes the half of its partial block that the other member finishes through LDS and finishes
+//     accumulator registers 8 m .. 8 m + 7 (tokens 16-step m of the block): R for those tokens;
+//   * S <- gam S + Z^T R for its own 32 rows: Z^T hi/lo against R hi/lo, three terms.
+// Three LDS-only barriers per step (S published, partial T exchanged, R published).  K and Z^T fragments have two
+// register sets (refilled two steps ahead), V^T and the per-token scalars one (refilled one step ahead).
+// Run decoding, identity columns and the composite-map record are those of the four-wavefront kernel above.
+template <bool GROUPED>
+__global__ __launch_bounds__(512) void gdn_walk8_kernel(GdnArgs a, const unsigned char *recs, int nblk, int groups, unsigned char *gmaps)
+{
+    constexpr int D = 128;
+    constexpr int KS = D / 16, NB = D / 32, NSL = D / 64;
+    constexpr int SROW = 2 * D + 16, RROW = 2 * CT + 16;
+    constexpr int S_BYTES = 64 * SROW, R_BYTES = 64 * RROW;
+    constexpr int TX_BYTES = 4 * 2 * 2 * 64 * 16;        // [block][writer][quad][lane] f32x4
+    constexpr int TROW = 2 * 64 + 16;                    // row of the [D][64] bf16 tile that transposes M_g
+    static_assert(2 * D * TROW <= 2 * S_BYTES + 2 * R_BYTES, "the transposing tiles reuse the exchange buffers");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S_BYTES + 2 * R_BYTES + TX_BYTES];
+    unsigned char *Shi = smem, *Slo = smem + S_BYTES, *Rhi = smem + 2 * S_BYTES, *Rlo = Rhi + R_BYTES;
+    f32x4 *Tx = (f32x4 *)(Rlo + R_BYTES);
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
+    const int rbT = wave & 1, cb = (wave >> 1) & 1, m = wave >> 2, rbF = (wave & 1) + 2 * m, blkid = wave & 3;
+    const int heads = a.B * a.H;
+    const int n_late = GROUPED ? (heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL : 0;
+    const bool late = (int)blockIdx.x < n_late;
+    const int id = late ? blockIdx.x : blockIdx.x - n_late;
+    const int xcd = id % kNumXcd, loc = id / kNumXcd;
+    const int units = late ? 2 * NSL : NSL;
+    const int unit = loc % units;
+    const int owner = (loc / units) * kNumXcd + xcd;
+    const int slice = unit % NSL;
+    const bool is_m = unit >= NSL;
+    int bh = owner, grp = 0, first = 0, n = nblk;
+    if constexpr (GROUPED) {
+        if (late) {
+            bh = owner / (groups - 1);
+            grp = 1 + owner % (groups - 1);
+        }
+        first = (int)((long long)grp * nblk / groups);
+        n = (int)((long long)(grp + 1) * nblk / groups) - first;
+    }
+    if (bh >= heads || n <= 0) return;
+    const int col = 32 * cb + c32, gcol = 64 * slice + col;          // column within the slice / within the state
+    float *Sg = a.S + (size_t)bh * D * D + gcol;
+
+    f32x16 s_acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = 32 * rbF + 8 * (r >> 2) + 4 * hh + (r & 3);
+        if (!GROUPED || grp == 0) s_acc[r] = Sg[(size_t)row * D];
+        else s_acc[r] = (is_m && row == gcol) ? 1.0f : 0.0f;
+    }
+    const float v_on = is_m ? 0.0f : 1.0f;               // the identity's columns take no V term
+    float gprod = 1.0f;
+
+    const unsigned char *ws = recs + ((size_t)bh * nblk + first) * gdn_ops_bytes(D);
+    bf16x8 kf[2][4], zh[2][4], zl[2][4], vf;
+    f32x4 be[2], se[2];
+    float gam[2];
+    auto rec_of = [&](int blk) { return ws + (size_t)(blk < n ? blk : n - 1) * gdn_ops_bytes(D); };   // past the end: the last one again (unused)
+    auto fetch_k = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const bf16x8 *Kf = (const bf16x8 *)rec_of(blk) + 2 * (CT * D / 8);
+        static_for<0, 4>([&](auto t_) { kf[bi][decltype(t_)::value] = Kf[(rbT * KS + 4 * m + decltype(t_)::value) * 64 + lane]; });
+    };
+    auto fetch_v = [&](int blk) __attribute__((always_inline)) {     // V^T of this member's 16 tokens, their scalars
+        const unsigned char *p = rec_of(blk);
+        const bf16x8 *Vf = (const bf16x8 *)p + 3 * (CT * D / 8);
+        const float *scal = (const float *)(p + (size_t)CT * D * 8);
+        vf = Vf[((2 * rbT + m) * NB + 2 * slice + cb) * 64 + lane];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            be[q] = *(const f32x4 *)(scal + 32 * rbT + 8 * (2 * m + q) + 4 * hh);
+            se[q] = *(const f32x4 *)(scal + CT + 32 * rbT + 8 * (2 * m + q) + 4 * hh);
+        }
+    };
+    auto fetch_z = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const unsigned char *p = rec_of(blk);
+        const bf16x8 *Zhi = (const bf16x8 *)p, *Zlo = Zhi + CT * D / 8;
+        static_for<0, 4>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            zh[bi][t] = Zhi[(rbF * 4 + t) * 64 + lane];
+            zl[bi][t] = Zlo[(rbF * 4 + t) * 64 + lane];
+        });
+        gam[bi] = *(const float *)(p + (size_t)CT * D * 8 + 2 * CT * 4);
+    };
+    auto step = [&](int blk, auto b_) __attribute__((always_inline)) {
+        constexpr int bi = decltype(b_)::value;
+        const float gam_cur = gam[bi];
+        // ---- this wavefront's 32 rows of the state slice to LDS, [column][row], hi and lo
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x4 h4, l4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x = s_acc[4 * q + e];
+                h4[e] = to_bf16(x);
+                l4[e] = to_bf16(x - (float)h4[e]);
+            }
+            const int off = col * SROW + 2 * (32 * rbF + 8 * q + 4 * hh);
+            *(bf16x4 *)(Shi + off) = h4;
+            *(bf16x4 *)(Slo + off) = l4;
+        }
+        lds_barrier();                                   // (not __syncthreads: the operand loads stay in flight)
+        // ---- partial T = K S over this member's 64 features, 32 tokens x 32 columns
+        f32x16 tp = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        static_for<0, 4>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            const bf16x8 sh = *(const bf16x8 *)(Shi + col * SROW + 32 * (4 * m + t) + 16 * hh);
+            const bf16x8 sl = *(const bf16x8 *)(Slo + col * SROW + 32 * (4 * m + t) + 16 * hh);
+            tp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sh, tp, 0, 0, 0);
+            tp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sl, tp, 0, 0, 0);
+        });
+        fetch_k(blk + 2, b_);
+        // the other member finishes registers 8 (1 - m) .. + 7: hand them over
+        {
+            f32x4 *dst = Tx + ((blkid * 2 + m) * 2) * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int r0 = 8 * (1 - m) + 4 * q;      // (m is uniform: both selections below are register moves)
+                dst[q * 64] = m ? f32x4{tp[0 + 4 * q], tp[1 + 4 * q], tp[2 + 4 * q], tp[3 + 4 * q]}
+                                : f32x4{tp[8 + 4 * q], tp[9 + 4 * q], tp[10 + 4 * q], tp[11 + 4 * q]};
+                (void)r0;
+            }
+        }
+        lds_barrier();
+        // ---- R = beta V + (-beta gamma- r) T for tokens 32 rbT + 16 m + 8 q + 4 hh + e, register 8 m + 4 q + e
+        {
+            const f32x4 *src = Tx + ((blkid * 2 + (1 - m)) * 2) * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const f32x4 other = src[q * 64];
+                bf16x4 h4, l4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float mine = m ? tp[8 + 4 * q + e] : tp[4 * q + e];
+                    const float v = (float)vf[4 * q + e];
+                    const float x = fmaf(se[q][e], mine + other[e], GROUPED ? v_on * be[q][e] * v : be[q][e] * v);
+                    h4[e] = to_bf16(x);
+                    l4[e] = to_bf16(x - (float)h4[e]);
+                }
+                const int off = col * RROW + 2 * (32 * rbT + 16 * m + 8 * q + 4 * hh);
+                *(bf16x4 *)(Rhi + off) = h4;
+                *(bf16x4 *)(Rlo + off) = l4;
+            }
+        }
+        fetch_v(blk + 1);
+        lds_barrier();
+        // ---- S <- gam S + Z^T R for this wavefront's 32 rows
+        f32x16 acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc1 = acc0;   // hi x hi, the two cross terms
+        static_for<0, 4>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            const bf16x8 rh = *(const bf16x8 *)(Rhi + col * RROW + 32 * t + 16 * hh);
+            const bf16x8 rl = *(const bf16x8 *)(Rlo + col * RROW + 32 * t + 16 * hh);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[bi][t], rh, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh[bi][t], rl, acc1, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl[bi][t], rh, acc1, 0, 0, 0);
+        });
+        fetch_z(blk + 2, b_);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[r] = fmaf(gam_cur, s_acc[r], acc0[r]) + acc1[r];
+        if constexpr (GROUPED) gprod *= gam_cur;
+    };
+
+    const std::integral_constant<int, 0> B0{};
+    const std::integral_constant<int, 1> B1{};
+    fetch_k(0, B0); fetch_v(0); fetch_z(0, B0);
+    fetch_k(1, B1); fetch_z(1, B1);
+    int blk = 0;
+#pragma unroll 1
+    for (; blk + 2 <= n; blk += 2) {
+        step(blk, B0);
+        step(blk + 1, B1);
+    }
+    if (blk < n) step(blk, B0);
+
+    if (!GROUPED || grp == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Sg[(size_t)(32 * rbF + 8 * (r >> 2) + 4 * hh + (r & 3)) * D] = s_acc[r];
+        return;
+    }
+    if constexpr (GROUPED) {
+        // the composite map of run grp >= 1 as one record of the composed-map format
+        unsigned char *rec = gmaps + ((size_t)bh * (groups - 1) + grp - 1) * gdn_block_bytes(D);
+        if (!is_m) {                                     // c_g, accumulator order [row block][column block][quad][lane]
+            f32x4 *Psi = (f32x4 *)(rec + (size_t)D * D * 4) + (rbF * NB + 2 * slice + cb) * 4 * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                Psi[q * 64] = f32x4{s_acc[4 * q], s_acc[4 * q + 1], s_acc[4 * q + 2], s_acc[4 * q + 3]};
+            if (slice == 0 && tid == 0) *(float *)(rec + (size_t)D * D * 8) = gprod;
+            return;
+        }
+        // M_g - gam_g I, columns 64 slice .. + 63: through LDS into A-fragment order (lane = row, eight
+        // columns of k-steps 4 slice .. 4 slice + 3 in k-slot order), hi and lo parts
+        __syncthreads();                                 // the exchange buffers are no longer read
+        unsigned char *Thi = smem, *Tlo = smem + D * TROW;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * rbF + 8 * (r >> 2) + 4 * hh + (r & 3);
+            const float x = s_acc[r] - (row == gcol ? gprod : 0.0f);
+            const bf16_t h = to_bf16(x);
+            *(bf16_t *)(Thi + row * TROW + 2 * col) = h;
+            *(bf16_t *)(Tlo + row * TROW + 2 * col) = to_bf16(x - (float)h);
+        }
+        __syncthreads();
+        bf16x8 *Ehi = (bf16x8 *)rec, *Elo = Ehi + D * D / 8;
+#pragma unroll
+        for (int i = 0; i < NB * 4 * 64 / 512; ++i) {    // NB * 4 * 64 fragment pieces, 512 threads
+            const int p = tid + 512 * i;
+            const int ln = p & 63, tl = (p >> 6) & 3, rb = p >> 8;
+            const int off = (32 * rb + (ln & 31)) * TROW + 2 * (16 * tl + 4 * (ln >> 5));
+            const bf16x4 h0 = *(const bf16x4 *)(Thi + off), h1 = *(const bf16x4 *)(Thi + off + 16);
+            const bf16x4 l0 = *(const bf16x4 *)(Tlo + off), l1 = *(const bf16x4 *)(Tlo + off + 16);
+            const int idx = (rb * KS + 4 * slice + tl) * 64 + ln;
+            Ehi[idx] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+            Elo[idx] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+}
+
 }  // namespace
 
 // Runs of blocks that are walked at the same time: as many as keep the walk within about one workgroup
@@ -745,13 +976,20 @@ static hipError_t launch_gdn(const GdnArgs &a, int nblk, unsigned nwg, hipStream
     // whole owners per XCD: ceil(owners / 8) on each of the 8 XCDs
     const unsigned owners8 = (unsigned)((heads + kNumXcd - 1) / kNumXcd * kNumXcd);
     if (groups == 1) {
+        if constexpr (D == 128)
+            return launch_kernel(gdn_walk8_kernel<false>, dim3(owners8 * NSL), dim3(512), stream, a, recs, nblk, 1,
+                                 (unsigned char *)nullptr);
         return launch_kernel(gdn_walk_kernel<D, false>, dim3(owners8 * NSL), dim3(256), stream, a, recs, nblk, 1,
                              (unsigned char *)nullptr);
     }
     // the runs after the first (c and M slices), then the first runs (c slices)
     const unsigned late8 = (unsigned)((heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd);
-    e = launch_kernel(gdn_walk_kernel<D, true>, dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), stream, a, recs, nblk,
-                      groups, gmaps);
+    if constexpr (D == 128)
+        e = launch_kernel(gdn_walk8_kernel<true>, dim3(late8 * 2 * NSL + owners8 * NSL), dim3(512), stream, a, recs, nblk,
+                          groups, gmaps);
+    else
+        e = launch_kernel(gdn_walk_kernel<D, true>, dim3(late8 * 2 * NSL + owners8 * NSL), dim3(256), stream, a, recs, nblk,
+                          groups, gmaps);
     if (e != hipSuccess) return e;
     // the composite maps of the later runs, applied in order to what the first run left in S
     return launch_kernel(gdn_apply_kernel<D>, dim3(owners8 * (D / 32)), dim3(2 * D), stream, a, (const unsigned char *)gmaps,
