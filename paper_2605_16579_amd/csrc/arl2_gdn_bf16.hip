@@ -58,6 +58,29 @@ struct GdnCfg {
 // Bytes of a composed D x D map record: -E hi, -E lo (bf16, fragment order), Psi (fp32, accumulator order), gam.
 __host__ __device__ constexpr size_t gdn_block_bytes(int D) { return (size_t)D * D * 8 + 16; }
 
+// Products over the 64 lanes of a wavefront, by multiplication only (a factor of exactly zero is handled):
+// lane l receives x_0 .. x_{l-1} (prefix) or x_{l+1} .. x_63 (suffix); six doubling steps each.
+__device__ __forceinline__ float lane_prefix_product(float x, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float y = __shfl_up(x, d, 64);
+        x *= lane >= d ? y : 1.f;
+    }
+    const float e = __shfl_up(x, 1, 64);
+    return lane == 0 ? 1.f : e;
+}
+__device__ __forceinline__ float lane_suffix_product(float x, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float y = __shfl_down(x, d, 64);
+        x *= lane + d < 64 ? y : 1.f;
+    }
+    const float e = __shfl_down(x, 1, 64);
+    return lane == 63 ? 1.f : e;
+}
+
 // ---- kernel 1: the affine map of one block of tokens -------------------------------------------------
 // Workspace per block of tokens: Z^T hi, Z^T lo (bf16, A fragments: [32-feature block][16-token step][lane]), K (bf16, A fragments:
 // [32-token block][k-step][lane]), V^T (bf16, fragments [16-token step][32-column block][lane], tokens in
@@ -130,21 +153,13 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
 
     // ---- 2. products of gates (wavefront 0) and the Gram matrix of the raw keys (three wavefronts)
     if (tid < CT) {
-        float gp = 1.f, tl = 1.f;                        // alpha_1 .. alpha_{i-1},  alpha_{i+1} .. alpha_64
-#pragma unroll
-        for (int q = 0; q < CT / 4; ++q) {
-            const f32x4 a4 = *(const f32x4 *)(sc_al + 4 * q);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int m = 4 * q + e;
-                gp *= m < tid ? a4[e] : 1.f;
-                tl *= m > tid ? a4[e] : 1.f;
-            }
-        }
+        // alpha_1 .. alpha_{i-1} and alpha_{i+1} .. alpha_64: exclusive prefix and suffix products over the lanes
+        const float al = sc_al[tid];
+        const float gp = lane_prefix_product(al, lane), tl = lane_suffix_product(al, lane);
         const float r = sc_r[tid], be = sc_be[tid];
         sc_tr[tid] = tl * r;
         sc_se[tid] = -(be * gp * r);
-        if (tid == CT - 1) sc_gam[0] = gp * sc_al[tid];
+        if (tid == CT - 1) sc_gam[0] = gp * al;
     }
     {
         const int ib = wave >> 1, jb = wave & 1;         // rows i, columns j of the 64 x 64 Gram matrix
@@ -174,13 +189,8 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
         float g[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) g[e] = As[(i0 + e) * C::AST + j];
-        float rho = 1.f;                                 // alpha_{j+1} .. alpha_{i0-1}
-#pragma unroll
-        for (int q = 0; q < 12; ++q) {
-            const f32x4 al4 = *(const f32x4 *)(sc_al + 4 * q);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) rho *= (4 * q + e > j && 4 * q + e < i0) ? al4[e] : 1.f;
-        }
+        // alpha_{j+1} .. alpha_{i0-1}: exclusive suffix product over the lanes of the gates before row i0
+        float rho = lane_suffix_product(j < i0 ? sc_al[j] : 1.f, lane);
         const float rj = sc_r[j];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
