@@ -16,9 +16,10 @@
 // and the per-token scalars, in the workspace in the operand-fragment order of kernel 2.  The Gram matrix
 // uses the raw bf16 keys (exact products) and is scaled in fp32; the triangular solve runs in fp32 in
 // blocks of 16 tokens, the diagonal systems on the vector ALU (one thread per feature), the off-diagonal
-// updates on MFMA with hi + lo splits.
-// Kernel 2 walks the blocks in order, one workgroup per 64 state columns, with two dependent contractions
-// per block (K S, then Z^T R).  With few heads the blocks of a head are cut into runs that are walked at
+// updates on MFMA with hi + lo splits.  K and V^T leave for the workspace as soon as the tiles are in LDS, Z
+// straight from the solver's registers.
+// Kernel 2 walks the blocks in order, one workgroup per 64 state columns (eight wavefronts at D = 128, four at
+// D = 64), with two dependent contractions per block (K S, then Z^T R).  With few heads the blocks of a head are cut into runs that are walked at
 // the same time: the first run on the real state, every later run on the columns of the identity and on
 // zero, which yields its composite map (M_g, c_g); kernel 3 applies those D x D maps in order.
 // (A first version composed E and Psi per block in kernel 1 and walked on those: twice the workspace
@@ -150,6 +151,27 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
         }
     }
     __syncthreads();
+
+    // The record of this block in the workspace.  K and V^T depend on the tiles alone: they leave now, in
+    // fragment order, and their stores drain while the solve runs.
+    unsigned char *rec = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_ops_bytes(D);
+    bf16x8 *Zhi = (bf16x8 *)rec, *Zlo = Zhi + CT * D / 8, *Kf = Zlo + CT * D / 8, *Vf = Kf + CT * D / 8;
+    float *scal = (float *)(rec + (size_t)CT * D * 8);
+    {
+        // K: fragment (rbT, t), lane (token c32, hh) = K[32 rbT + c32][16 t + 8 hh + 0..7]
+        for (int p = tid; p < 2 * C::KS * 64; p += NTA) {
+            const int ln = p & 63, t = (p >> 6) % C::KS, rbT = p / (64 * C::KS);
+            Kf[p] = *(const bf16x8 *)(R0 + (32 * rbT + (ln & 31)) * C::ROW + 2 * (16 * t + 8 * (ln >> 5)));
+        }
+        // V^T: fragment (t, eblk), lane (column c32, hh) = V[16 t + 8 (j / 4) + 4 hh + j % 4][32 eblk + c32].
+        // A token-major tile is read through the transposing LDS read: lanes (column c32, hh) get eight tokens of
+        // their column, k-slot j <-> token 16 t + 8 (j / 4) + 4 hh + j % 4 (the order of accumulator registers).
+        const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+        for (int f = wave; f < 4 * C::NB; f += NTA / 64) {
+            const int t = f / C::NB, eblk = f % C::NB;
+            Vf[f * 64 + lane] = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * eblk, 8 * C::ROW);
+        }
+    }
 
     // ---- 2. products of gates (wavefront 0) and the Gram matrix of the raw keys (three wavefronts)
     if (tid < CT) {
@@ -299,54 +321,24 @@ __global__ __launch_bounds__(NTA, 2) void gdn_block_kernel(GdnArgs a, int nblk)
             }
         });
     }
-    __syncthreads();                                     // A is dead: R2, R3 become the Z^T tiles
-
-    // Z^T scaled per token (sc points at 64 scales), split into bf16 hi (R2) + lo (R3), [feature][token]
-    auto put_z = [&](const float *sc) {
-        if (tid < D) {
+    // Z^T leaves straight from the registers of the feature threads, split into bf16 hi + lo:
+    // fragment (rb, t), lane (feature c32, hh) = Z^T[32 rb + c32][16 t + 8 hh + 0..7]; consecutive threads
+    // (features) write consecutive 16-byte pieces
+    if (tid < D) {
+        const int rb = tid >> 5, f32 = tid & 31;
 #pragma unroll
-            for (int q = 0; q < CT / 8; ++q) {
-                const f32x4 s0 = *(const f32x4 *)(sc + 8 * q), s1 = *(const f32x4 *)(sc + 8 * q + 4);
-                bf16x8 h8, l8;
+        for (int q = 0; q < CT / 8; ++q) {               // q = 2 t + hh
+            bf16x8 h8, l8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float x = (e < 4 ? s0[e] : s1[e - 4]) * z[8 * q + e];   // (sc == sc_one: times one)
-                    h8[e] = to_bf16(x);
-                    l8[e] = to_bf16(x - (float)h8[e]);
-                }
-                *(bf16x8 *)(R2 + tid * C::ZROW + 16 * q) = h8;
-                *(bf16x8 *)(R3 + tid * C::ZROW + 16 * q) = l8;
+            for (int e = 0; e < 8; ++e) {
+                const float x = z[8 * q + e];
+                h8[e] = to_bf16(x);
+                l8[e] = to_bf16(x - (float)h8[e]);
             }
+            const int p = (rb * 4 + (q >> 1)) * 64 + f32 + 32 * (q & 1);
+            Zhi[p] = h8;
+            Zlo[p] = l8;
         }
-    };
-    // A token-major tile is read through the transposing LDS read: lanes (column c32, hh) get eight tokens
-    // of their column, k-slot j <-> token 16 t + 8 (j / 4) + 4 hh + j % 4 (the order of accumulator registers).
-    const int tr_off = (((lane & 15) >> 2) + 4 * hh) * C::ROW + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
-
-    // sc_tr is no longer needed: it becomes an array of ones, so that put_z writes Z itself
-    if (tid < CT) sc_tr[tid] = 1.0f;
-    __syncthreads();
-    put_z(sc_tr);
-    __syncthreads();
-    unsigned char *rec = (unsigned char *)a.workspace + ((size_t)bh * nblk + blk) * gdn_ops_bytes(D);
-    bf16x8 *Zhi = (bf16x8 *)rec, *Zlo = Zhi + CT * D / 8, *Kf = Zlo + CT * D / 8, *Vf = Kf + CT * D / 8;
-    float *scal = (float *)(rec + (size_t)CT * D * 8);
-    // Z^T: fragment (rb, t), lane (feature c32, hh) = Z^T[32 rb + c32][16 t + 8 hh + 0..7]
-    for (int p = tid; p < C::NB * 4 * 64; p += NTA) {
-        const int ln = p & 63, t = (p >> 6) & 3, rb = p >> 8;
-        const int off = (32 * rb + (ln & 31)) * C::ZROW + 2 * (16 * t + 8 * (ln >> 5));
-        Zhi[p] = *(const bf16x8 *)(R2 + off);
-        Zlo[p] = *(const bf16x8 *)(R3 + off);
-    }
-    // K: fragment (rbT, t), lane (token c32, hh) = K[32 rbT + c32][16 t + 8 hh + 0..7]
-    for (int p = tid; p < 2 * C::KS * 64; p += NTA) {
-        const int ln = p & 63, t = (p >> 6) % C::KS, rbT = p / (64 * C::KS);
-        Kf[p] = *(const bf16x8 *)(R0 + (32 * rbT + (ln & 31)) * C::ROW + 2 * (16 * t + 8 * (ln >> 5)));
-    }
-    // V^T: fragment (t, eblk), lane (column c32, hh) = V[16 t + 8 (j / 4) + 4 hh + j % 4][32 eblk + c32]
-    for (int f = wave; f < 4 * C::NB; f += NTA / 64) {
-        const int t = f / C::NB, eblk = f % C::NB;
-        Vf[f * 64 + lane] = lds_read_tr_pair(R1 + tr_off + 16 * t * C::ROW + 64 * eblk, 8 * C::ROW);
     }
     if (tid < CT) {
         scal[tid] = sc_be[tid];
