@@ -723,12 +723,12 @@ __global__ __launch_bounds__(256) void gdn_walk_kernel(GdnArgs a, const unsigned
 // is half as long:
 //   * state: wavefront w owns rows 32 rbF .. + 31 (rbF = w % 2 + 2 (w / 4)) of column block cb = w / 2 % 2;
 //   * T = K S: the 32 x 32 block (token block rbT = w % 2, column block cb) belongs to the pair (w, w + 4);
-//     member m = w / 4 contracts over features 64 m .. 64 m + 63 (K raw against S hi and S lo, one accumulator),
-//     passes the half of its partial block that the other member finishes through LDS and finishes
-//     accumulator registers 8 m .. 8 m + 7 (tokens 16-step m of the block): R for those tokens;
+//     member m = w / 4 takes tokens 16 m .. 16 m + 15 of it, as 16 x 16 x 32 MFMAs over two column halves (K raw
+//     against S hi and S lo, one accumulator per half; the K operand is gathered from the record's 32 x 32 x 16
+//     fragments, 16 bytes per lane), and forms R for those tokens;
 //   * S <- gam S + Z^T R for its own 32 rows: Z^T hi/lo against R hi/lo, three terms.
-// Three LDS-only barriers per step (S published, partial T exchanged, R published).  K and Z^T fragments have two
-// register sets (refilled two steps ahead), V^T and the per-token scalars one (refilled one step ahead).
+// Two LDS-only barriers per step (S published, R published).  K and Z^T fragments have two register sets
+// (refilled two steps ahead), V^T and the per-token scalars one (refilled one step ahead).
 // Run decoding, identity columns and the composite-map record are those of the four-wavefront kernel above.
 template <bool GROUPED>
 __global__ __launch_bounds__(512) void gdn_walk8_kernel(GdnArgs a, const unsigned char *recs, int nblk, int groups, unsigned char *gmaps)
@@ -737,16 +737,15 @@ __global__ __launch_bounds__(512) void gdn_walk8_kernel(GdnArgs a, const unsigne
     constexpr int KS = D / 16, NB = D / 32, NSL = D / 64;
     constexpr int SROW = 2 * D + 16, RROW = 2 * CT + 16;
     constexpr int S_BYTES = 64 * SROW, R_BYTES = 64 * RROW;
-    constexpr int TX_BYTES = 4 * 2 * 2 * 64 * 16;        // [block][writer][quad][lane] f32x4
     constexpr int TROW = 2 * 64 + 16;                    // row of the [D][64] bf16 tile that transposes M_g
     static_assert(2 * D * TROW <= 2 * S_BYTES + 2 * R_BYTES, "the transposing tiles reuse the exchange buffers");
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S_BYTES + 2 * R_BYTES + TX_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S_BYTES + 2 * R_BYTES];
     unsigned char *Shi = smem, *Slo = smem + S_BYTES, *Rhi = smem + 2 * S_BYTES, *Rlo = Rhi + R_BYTES;
-    f32x4 *Tx = (f32x4 *)(Rlo + R_BYTES);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hh = lane >> 5, c32 = lane & 31;
-    const int rbT = wave & 1, cb = (wave >> 1) & 1, m = wave >> 2, rbF = (wave & 1) + 2 * m, blkid = wave & 3;
+    const int rbT = wave & 1, cb = (wave >> 1) & 1, m = wave >> 2, rbF = (wave & 1) + 2 * m;
+    const int c16 = lane & 15, g = lane >> 4;            // operand coordinates of the 16 x 16 x 32 MFMA
     const int heads = a.B * a.H;
     const int n_late = GROUPED ? (heads * (groups - 1) + kNumXcd - 1) / kNumXcd * kNumXcd * 2 * NSL : 0;
     const bool late = (int)blockIdx.x < n_late;
@@ -781,25 +780,32 @@ __global__ __launch_bounds__(512) void gdn_walk8_kernel(GdnArgs a, const unsigne
     float gprod = 1.0f;
 
     const unsigned char *ws = recs + ((size_t)bh * nblk + first) * gdn_ops_bytes(D);
-    bf16x8 kf[2][4], zh[2][4], zl[2][4], vf;
-    f32x4 be[2], se[2];
+    bf16x8 kf[2][4], zh[2][4], zl[2][4];
+    bf16x4 vf[2];
+    f32x4 be, se;
     float gam[2];
     auto rec_of = [&](int blk) { return ws + (size_t)(blk < n ? blk : n - 1) * gdn_ops_bytes(D); };   // past the end: the last one again (unused)
     auto fetch_k = [&](int blk, auto b_) __attribute__((always_inline)) {
         constexpr int bi = decltype(b_)::value;
         const bf16x8 *Kf = (const bf16x8 *)rec_of(blk) + 2 * (CT * D / 8);
-        static_for<0, 4>([&](auto t_) { kf[bi][decltype(t_)::value] = Kf[(rbT * KS + 4 * m + decltype(t_)::value) * 64 + lane]; });
+        // A operand of feature step s (32 features): lane (token 16 m + c16, g) holds K[..][32 s + 8 g + 0..7], which
+        // the record keeps in its 32 x 32 x 16 fragment (rbT, 2 s + g / 2) at lane 16 m + c16 + 32 (g % 2)
+        static_for<0, 4>([&](auto s_) {
+            constexpr int sx = decltype(s_)::value;
+            kf[bi][sx] = Kf[(rbT * KS + 2 * sx + (g >> 1)) * 64 + 16 * m + c16 + 32 * (g & 1)];
+        });
     };
     auto fetch_v = [&](int blk) __attribute__((always_inline)) {     // V^T of this member's 16 tokens, their scalars
         const unsigned char *p = rec_of(blk);
         const bf16x8 *Vf = (const bf16x8 *)p + 3 * (CT * D / 8);
         const float *scal = (const float *)(p + (size_t)CT * D * 8);
-        vf = Vf[((2 * rbT + m) * NB + 2 * slice + cb) * 64 + lane];
+        // tokens 4 g + 0..3 of the 16-token step 2 rbT + m, columns 16 ch + c16 of the block: k-slots 4 (g / 2) + 0..3
+        // of lane 16 ch + c16 + 32 (g % 2) in the record's V^T fragment
+        const bf16x4 *V4 = (const bf16x4 *)(Vf + ((2 * rbT + m) * NB + 2 * slice + cb) * 64);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            be[q] = *(const f32x4 *)(scal + 32 * rbT + 8 * (2 * m + q) + 4 * hh);
-            se[q] = *(const f32x4 *)(scal + CT + 32 * rbT + 8 * (2 * m + q) + 4 * hh);
-        }
+        for (int ch = 0; ch < 2; ++ch) vf[ch] = V4[2 * (16 * ch + c16 + 32 * (g & 1)) + (g >> 1)];
+        be = *(const f32x4 *)(scal + 32 * rbT + 16 * m + 4 * g);
+        se = *(const f32x4 *)(scal + CT + 32 * rbT + 16 * m + 4 * g);
     };
     auto fetch_z = [&](int blk, auto b_) __attribute__((always_inline)) {
         constexpr int bi = decltype(b_)::value;
@@ -830,47 +836,33 @@ __global__ __launch_bounds__(512) void gdn_walk8_kernel(GdnArgs a, const unsigne
             *(bf16x4 *)(Slo + off) = l4;
         }
         lds_barrier();                                   // (not __syncthreads: the operand loads stay in flight)
-        // ---- partial T = K S over this member's 64 features, 32 tokens x 32 columns
-        f32x16 tp = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        static_for<0, 4>([&](auto t_) {
-            constexpr int t = decltype(t_)::value;
-            const bf16x8 sh = *(const bf16x8 *)(Shi + col * SROW + 32 * (4 * m + t) + 16 * hh);
-            const bf16x8 sl = *(const bf16x8 *)(Slo + col * SROW + 32 * (4 * m + t) + 16 * hh);
-            tp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sh, tp, 0, 0, 0);
-            tp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t], sl, tp, 0, 0, 0);
+        // ---- T = K S for this member's 16 tokens x 32 columns, all 128 features: 16 x 16 x 32 MFMAs, two column
+        // halves; lane (column c16, g) ends up with tokens 4 g + 0..3 of both halves
+        f32x4 tq[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        static_for<0, 4>([&](auto s_) {
+            constexpr int sx = decltype(s_)::value;
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch) {
+                const int o = (32 * cb + 16 * ch + c16) * SROW + 64 * sx + 16 * g;
+                tq[ch] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[bi][sx], *(const bf16x8 *)(Shi + o), tq[ch], 0, 0, 0);
+                tq[ch] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[bi][sx], *(const bf16x8 *)(Slo + o), tq[ch], 0, 0, 0);
+            }
         });
         fetch_k(blk + 2, b_);
-        // the other member finishes registers 8 (1 - m) .. + 7: hand them over
-        {
-            f32x4 *dst = Tx + ((blkid * 2 + m) * 2) * 64 + lane;
+        // ---- R = beta V + (-beta gamma- r) T for tokens 32 rbT + 16 m + 4 g + e
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int r0 = 8 * (1 - m) + 4 * q;      // (m is uniform: both selections below are register moves)
-                dst[q * 64] = m ? f32x4{tp[0 + 4 * q], tp[1 + 4 * q], tp[2 + 4 * q], tp[3 + 4 * q]}
-                                : f32x4{tp[8 + 4 * q], tp[9 + 4 * q], tp[10 + 4 * q], tp[11 + 4 * q]};
-                (void)r0;
+        for (int ch = 0; ch < 2; ++ch) {
+            bf16x4 h4, l4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = (float)vf[ch][e];
+                const float x = fmaf(se[e], tq[ch][e], GROUPED ? v_on * be[e] * v : be[e] * v);
+                h4[e] = to_bf16(x);
+                l4[e] = to_bf16(x - (float)h4[e]);
             }
-        }
-        lds_barrier();
-        // ---- R = beta V + (-beta gamma- r) T for tokens 32 rbT + 16 m + 8 q + 4 hh + e, register 8 m + 4 q + e
-        {
-            const f32x4 *src = Tx + ((blkid * 2 + (1 - m)) * 2) * 64 + lane;
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const f32x4 other = src[q * 64];
-                bf16x4 h4, l4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float mine = m ? tp[8 + 4 * q + e] : tp[4 * q + e];
-                    const float v = (float)vf[4 * q + e];
-                    const float x = fmaf(se[q][e], mine + other[e], GROUPED ? v_on * be[q][e] * v : be[q][e] * v);
-                    h4[e] = to_bf16(x);
-                    l4[e] = to_bf16(x - (float)h4[e]);
-                }
-                const int off = col * RROW + 2 * (32 * rbT + 16 * m + 8 * q + 4 * hh);
-                *(bf16x4 *)(Rhi + off) = h4;
-                *(bf16x4 *)(Rlo + off) = l4;
-            }
+            const int off = (32 * cb + 16 * ch + c16) * RROW + 2 * (32 * rbT + 16 * m + 4 * g);
+            *(bf16x4 *)(Rhi + off) = h4;
+            *(bf16x4 *)(Rlo + off) = l4;
         }
         fetch_v(blk + 1);
         lds_barrier();
