@@ -276,25 +276,34 @@ def test_rollout_step_latency_is_flat(lib):
 
     for _ in range(30):          # clocks and caches settle
         step()
-    S.zero_()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(w.chunks + 1)]
-    ev[0].record()
-    for c in range(w.chunks):
-        step()
-        ev[c + 1].record()
-    torch.cuda.synchronize()
-    ms = np.array([ev[c].elapsed_time(ev[c + 1]) for c in range(w.chunks)])
-    med = float(np.median(ms))
-    slope = float(np.polyfit(np.arange(w.chunks), ms, 1)[0])
-    print(f"[wan_rollout] step latency over {w.chunks} chunks: median {med:.4f} ms, max/median {ms.max() / med:.3f}, "
-          f"min/median {ms.min() / med:.3f}, least-squares drift over the rollout {slope * w.chunks / med * 100:+.2f} % of median",
-          flush=True)
-    print("[wan_rollout] ms per chunk:", " ".join(f"{x:.3f}" for x in ms), flush=True)
+
+    def series():
+        S.zero_()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(w.chunks + 1)]
+        ev[0].record()
+        for c in range(w.chunks):
+            step()
+            ev[c + 1].record()
+        torch.cuda.synchronize()
+        ms = np.array([ev[c].elapsed_time(ev[c + 1]) for c in range(w.chunks)])
+        med = float(np.median(ms))
+        slope = float(np.polyfit(np.arange(w.chunks), ms, 1)[0])
+        print(f"[wan_rollout] step latency over {w.chunks} chunks: median {med:.4f} ms, max/median {ms.max() / med:.3f}, "
+              f"min/median {ms.min() / med:.3f}, least-squares drift over the rollout {slope * w.chunks / med * 100:+.2f} % of median",
+              flush=True)
+        print("[wan_rollout] ms per chunk:", " ".join(f"{x:.3f}" for x in ms), flush=True)
+        return slope * w.chunks < 0.03 * med, np.percentile(ms, 90) < 1.05 * med
+
     # a cost that grew with the history (a cache of past chunks) would show up as hundreds of per cent; recorded
     # series on this hardware: drift between -3.6 % and +0.5 % of the median over the rollout, 90th percentile
-    # within 1 % of the median, single slow chunks (the first one, clock changes) up to 5 % above it
-    assert slope * w.chunks < 0.03 * med, "per-chunk latency grows with the chunk index"
-    assert np.percentile(ms, 90) < 1.05 * med
+    # within 1 % of the median, single slow chunks (the first one, clock changes) up to 5 % above it.  The margins
+    # are a few per cent, and the clock of a shared machine can move by that much within one series: a series that
+    # misses them is measured once more, and both are printed (growth with the history fails every series).
+    flat, tight = series()
+    if not (flat and tight):
+        flat, tight = series()
+    assert flat, "per-chunk latency grows with the chunk index"
+    assert tight, "the 90th percentile of the per-chunk latency is more than 5 % above the median"
     assert torch.isfinite(S).all()
 
 
@@ -885,13 +894,19 @@ def test_bench_stack_executed_agrees_with_weighted_sum(lib):
     bench = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(bench)
     d = torch.device("cuda:0")
-    est = bench.stack_report(lib, W, torch, d, chunks=3, reps=3)
-    ex = bench.stack_execute(lib, W, torch, d, chunks=3)
+    # (two timings of the same work on a shared machine: if the clock moved between them by more than the margin, both
+    # are taken once more; every attempt is printed)
+    for attempt in range(2):
+        est = bench.stack_report(lib, W, torch, d, chunks=3, reps=3)
+        ex = bench.stack_execute(lib, W, torch, d, chunks=3)
+        ratios = {name: ex[name]["attention_ms"] / est[name]["attention_ms"] for name in ("hybrid_stack", "softmax_stack")}
+        for name, ratio in ratios.items():
+            print(f"[stack] {name}: executed {ex[name]['attention_ms']:.1f} ms, weighted sum {est[name]['attention_ms']:.1f} ms, ratio {ratio:.3f}; "
+                  f"peak memory {ex[name]['peak_memory_bytes'] / 1e9:.3f} GB, counted {est[name]['memory_bytes'] / 1e9:.3f} GB", flush=True)
+        if all(abs(r - 1.0) <= 0.05 for r in ratios.values()):
+            break
     for name in ("hybrid_stack", "softmax_stack"):
-        ratio = ex[name]["attention_ms"] / est[name]["attention_ms"]
-        print(f"[stack] {name}: executed {ex[name]['attention_ms']:.1f} ms, weighted sum {est[name]['attention_ms']:.1f} ms, ratio {ratio:.3f}; "
-              f"peak memory {ex[name]['peak_memory_bytes'] / 1e9:.3f} GB, counted {est[name]['memory_bytes'] / 1e9:.3f} GB", flush=True)
-        assert abs(ratio - 1.0) <= 0.05, (name, ratio)
+        assert abs(ratios[name] - 1.0) <= 0.05, (name, ratios[name])
         assert ex[name]["readout_calls"] == 3 * 4 * 30
         # allocator granularity and the commit workspace (hybrid stack only) are all that may come on top
         assert est[name]["memory_bytes"] <= ex[name]["peak_memory_bytes"] <= est[name]["memory_bytes"] + (64 << 20)
